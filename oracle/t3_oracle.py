@@ -1,0 +1,195 @@
+"""ctypes front end of the CPU oracle (oracle/t3_oracle.c) plus the composition of
+its steps into the whole fused path.
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
+CPU-baseline leg of the benchmark; never by the product package.  It imports
+nothing from the product package either: inputs arrive as numpy arrays.
+
+What the path computes (T3, arXiv 2401.16677): rank r of a P-way tensor-parallel
+group multiplies its K-slice (Sec. 2.4), the M x N partial output is cut into P
+column chunks that are produced in the staggered ring order (Sec. 4.1, 4.4),
+each element is added to the partial received from upstream (Sec. 2.3), all
+chunks but the last produced are handed on to the downstream neighbour once a
+tracker has seen every update of the chunk (Sec. 4.2), and the last chunk stays
+on the rank fully reduced.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libt3_oracle.so")
+_lib = None
+
+B_NK = 0  # B stored N x K, K contiguous
+B_KN = 1  # B stored K x N, N contiguous
+
+_c_i32 = ctypes.c_int32
+_c_i64 = ctypes.c_int64
+_p = ctypes.c_void_p
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(_LIB_PATH)
+        L.t3o_num_threads.restype = _c_i32
+        L.t3o_chunk_order.argtypes = [_c_i32, _c_i32, _p, _p]
+        L.t3o_gemm_rows.argtypes = [_c_i32, _c_i32, _c_i32, _p, _c_i64, _p, _c_i64, _c_i32,
+                                    _p, _c_i32, _p]
+        L.t3o_reduce_rows.argtypes = [_c_i32, _c_i32, _c_i32, _p, _p, _c_i64, _p, _c_i32,
+                                      _p, _c_i64]
+        L.t3o_tile_of.argtypes = [_c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_i64,
+                                  _p, _p, _p, _p]
+        L.t3o_track.argtypes = [_c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _p, _c_i64,
+                                _p, _p, _p, _p]
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(_p)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what}: bad argument (rc={rc})")
+
+
+def num_threads():
+    return int(lib().t3o_num_threads())
+
+
+def chunk_order(P, r):
+    """Ring order of rank r and the chunk it keeps (Sec. 4.1, Sec. 4.4)."""
+    order = np.zeros(max(P, 1), dtype=np.int32)
+    own = _c_i32(-1)
+    _check(lib().t3o_chunk_order(P, r, _ptr(order), ctypes.byref(own)), "chunk_order")
+    return order[:P].copy(), int(own.value)
+
+
+def gemm_rows(A_bits, B_bits, b_layout=B_NK, rows=None):
+    """fp64 sliced GEMM (Sec. 2.4) for all rows or the listed rows.
+
+    A_bits: uint16 (M, K) bf16 bit patterns; B_bits: uint16 (N, K) for B_NK or
+    (K, N) for B_KN.  Returns float64 (nrows, N).
+    """
+    A_bits = np.ascontiguousarray(A_bits, dtype=np.uint16)
+    B_bits = np.ascontiguousarray(B_bits, dtype=np.uint16)
+    M, K = A_bits.shape
+    if b_layout == B_NK:
+        N, Kb = B_bits.shape
+    else:
+        Kb, N = B_bits.shape
+    if Kb != K:
+        raise ValueError("A and B disagree on K")
+    if rows is None:
+        rows_arr, nrows = None, M
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int32)
+        nrows = rows_arr.shape[0]
+    C = np.empty((nrows, N), dtype=np.float64)
+    _check(lib().t3o_gemm_rows(M, N, K, _ptr(A_bits), A_bits.shape[1], _ptr(B_bits),
+                               B_bits.shape[1], int(b_layout), _ptr(rows_arr), nrows, _ptr(C)),
+           "gemm_rows")
+    return C
+
+
+def reduce_rows(C, incoming, P, skip_chunk=-1, rows=None):
+    """S = fl32(incoming + C) on all or the listed rows (Sec. 2.3)."""
+    C = np.ascontiguousarray(C, dtype=np.float64)
+    incoming = np.ascontiguousarray(incoming, dtype=np.float32)
+    nrows, N = C.shape
+    rows_arr = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    if rows_arr is None and incoming.shape[0] != nrows:
+        raise ValueError("incoming and C disagree on rows")
+    S = np.empty((nrows, N), dtype=np.float32)
+    _check(lib().t3o_reduce_rows(N, P, skip_chunk, _ptr(C), _ptr(incoming), incoming.shape[1],
+                                 _ptr(rows_arr), nrows, _ptr(S), N), "reduce_rows")
+    return S
+
+
+def tile_of(M, N, P, r, tile_m, tile_n, t):
+    """Issue index t -> (stage s, chunk c, tile row mi, tile column nj inside the chunk)."""
+    s, c, mi, nj = _c_i32(), _c_i32(), _c_i32(), _c_i32()
+    _check(lib().t3o_tile_of(M, N, P, r, tile_m, tile_n, t, ctypes.byref(s), ctypes.byref(c),
+                             ctypes.byref(mi), ctypes.byref(nj)), "tile_of")
+    return int(s.value), int(c.value), int(mi.value), int(nj.value)
+
+
+def tiles_per_chunk(M, N, P, tile_m, tile_n):
+    W = N // P
+    return -(-M // tile_m) * -(-W // tile_n)
+
+
+def track(M, N, P, r, tile_m, tile_n, landed):
+    """Replay tile landings (issue indices, in landing order) through the tracker (Sec. 4.2)."""
+    landed = np.ascontiguousarray(landed, dtype=np.int64)
+    counter = np.zeros(P, dtype=np.uint32)
+    ready = np.zeros(P, dtype=np.uint32)
+    queue = np.zeros(P, dtype=np.uint32)
+    qlen = ctypes.c_uint32(0)
+    _check(lib().t3o_track(M, N, P, r, tile_m, tile_n, _ptr(landed), landed.shape[0],
+                           _ptr(counter), _ptr(ready), _ptr(queue), ctypes.byref(qlen)), "track")
+    return {"counter": counter, "ready": ready, "queue": queue, "queue_len": int(qlen.value)}
+
+
+def executed_mask(M, N, P, r, tile_m, tile_n, tile_limit):
+    """Boolean (M, N): element lies in one of the first tile_limit tiles of the issue order."""
+    W = N // P
+    T = P * tiles_per_chunk(M, N, P, tile_m, tile_n)
+    L = T if tile_limit < 0 else min(tile_limit, T)
+    mask = np.zeros((M, N), dtype=bool)
+    for t in range(L):
+        _, c, mi, nj = tile_of(M, N, P, r, tile_m, tile_n, t)
+        m0, n0 = mi * tile_m, c * W + nj * tile_n
+        mask[m0:min(m0 + tile_m, M), n0:min(n0 + tile_n, (c + 1) * W)] = True
+    return mask, L
+
+
+def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
+               tile_limit=-1, step0_store_only=False, fwd_direct=False, fwd_init=None):
+    """The whole path for one rank, by the definition.
+
+    Returns a dict with
+      R        (M, N) fp32   local buffer after the call
+      fwd      (P-1, M, W)   forward slots, slot s holds chunk order[s]
+      owned    (M, W)        the chunk the rank keeps = R[:, own*W:(own+1)*W]
+      order, own, counter, ready, queue (in issue order), queue_len, tiles_per_chunk
+    Default release mode: every executed tile is added in place into R and a chunk
+    is copied to its forward slot once complete.  fwd_direct: sums of forwarded
+    chunks go straight to the forward slot and R keeps the incoming data there.
+    Elements outside executed tiles keep their initial contents.
+    """
+    incoming = np.ascontiguousarray(incoming, dtype=np.float32)
+    M, N = incoming.shape
+    if N % P:
+        raise ValueError("N must be a multiple of P")
+    W = N // P
+    order, own = chunk_order(P, r)
+    C = gemm_rows(A_bits, B_bits, b_layout)
+    S = reduce_rows(C, incoming, P, skip_chunk=int(order[0]) if step0_store_only else -1)
+    mask, L = executed_mask(M, N, P, r, tile_m, tile_n, tile_limit)
+    trk = track(M, N, P, r, tile_m, tile_n, np.arange(L, dtype=np.int64))
+
+    fwd = (np.zeros((max(P - 1, 0), M, W), dtype=np.float32) if fwd_init is None
+           else np.array(fwd_init, dtype=np.float32, copy=True))
+    R = incoming.copy()
+    for s in range(P):
+        c = int(order[s])
+        cols = slice(c * W, (c + 1) * W)
+        if c == own or not fwd_direct:
+            R[:, cols] = np.where(mask[:, cols], S[:, cols], incoming[:, cols])
+        if c != own:
+            if fwd_direct:
+                fwd[s] = np.where(mask[:, cols], S[:, cols], fwd[s])
+            elif trk["ready"][c]:
+                fwd[s] = S[:, cols]
+    out = dict(trk)
+    out.update(R=R, fwd=fwd, owned=R[:, own * W:(own + 1) * W].copy(), order=order, own=own,
+               tiles_per_chunk=tiles_per_chunk(M, N, P, tile_m, tile_n), executed=L)
+    return out
