@@ -1,0 +1,158 @@
+/*
+ * t3.h -- C ABI of the MI355X (gfx950) implementation of one tensor-parallel rank's
+ * fused "sliced producer GEMM + ring reduce-scatter reduction + track & trigger" path
+ * of T3 (arXiv 2401.16677).
+ *
+ * The problem, in the paper's terms: rank `rank` of a `tp`-way tensor-parallel group
+ * holds a K-slice of a row-parallel layer (output projection or FC-2, Sec. 2.4) and
+ * produces a full-size M x N *partial* output C = A.B.  The ring reduce-scatter that
+ * follows cuts the output into `tp` column chunks of width W = N/tp (Sec. 2.3); a rank
+ * produces the chunks in the staggered ring order order[s] = (rank + s) mod tp
+ * (Sec. 4.1, Sec. 4.4), adds each to the partial received from its upstream
+ * neighbour, hands every chunk but the last on to its downstream neighbour once all
+ * of the chunk's updates have landed (the tracker and DMA trigger of Sec. 4.2), and
+ * keeps the last one, own = (rank - 1) mod tp, fully reduced.
+ *
+ * On one GPU the upstream data is a caller-seeded "incoming" buffer R and the
+ * downstream neighbour's memory is a forward buffer `fwd`.
+ *
+ * Conventions for every entry point
+ *  - Pointers named A, B, C, R, fwd, track are DEVICE pointers owned by the caller.
+ *    The library allocates and frees nothing and keeps no mutable global state.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *    asynchronous on that stream and never synchronise it.
+ *  - Arguments are validated on the host before anything is enqueued; on any status
+ *    other than T3_OK nothing was launched and no buffer was touched.
+ *  - A and B are read only.  Buffers must not overlap each other.
+ */
+#ifndef T3_H
+#define T3_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  T3_OK = 0,
+  T3_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+  T3_ERR_BAD_SHAPE = 2,   /* M,N,K < 0; tp < 1; rank outside [0,tp); N % tp != 0; ld < width */
+  T3_ERR_BAD_TILE = 3,    /* (tile_m, tile_n) is not one of the supported tile shapes     */
+  T3_ERR_ALIGN = 4,       /* pointer, leading dimension or width breaks an alignment rule */
+  T3_ERR_UNSUPPORTED = 5, /* valid request this build does not implement                  */
+  T3_ERR_HIP = 6          /* the HIP runtime refused the launch; see t3_last_hip_error()  */
+} t3_status;
+
+typedef enum {
+  T3_B_NK = 0, /* B stored N x K, K contiguous: element (k,n) at B[n*ldb + k] (forward-pass weight) */
+  T3_B_KN = 1  /* B stored K x N, N contiguous: element (k,n) at B[k*ldb + n]                       */
+} t3_b_layout;
+
+/* flags */
+#define T3_FLAG_STEP0_STORE_ONLY 1u /* the first chunk produced (order[0]) has no upstream data yet:
+                                       it is stored, not added to R (Sec. 4.1, Sec. 4.4)             */
+#define T3_FLAG_FWD_DIRECT 2u       /* sums of forwarded chunks are written straight into their
+                                       forward slot (the remote-mapped store of Sec. 4.4, the
+                                       direct reduce-scatter of Sec. 7.1); R keeps the incoming
+                                       data there                                                    */
+
+typedef struct {
+  int32_t M, N, K;        /* tokens, hidden size, slice width of this rank                           */
+  int32_t tp, rank;       /* ring size and this rank's position                                      */
+  int32_t tile_m, tile_n; /* output tile = tracker granularity; 0,0 = t3_default_tile()              */
+  int32_t b_layout;       /* t3_b_layout                                                             */
+  int64_t lda, ldb;       /* leading dimensions of A (>= K) and B (>= K for NK, >= N for KN), in
+                             bf16 elements, multiples of 8                                           */
+  int64_t ldr;            /* leading dimension of R (>= N), in floats, multiple of 4                 */
+  int64_t ldc;            /* leading dimension of C (>= N) for t3_gemm / t3_rs_reduce, multiple of 4 */
+  int64_t tile_limit;     /* < 0: run every tile.  Otherwise only tiles whose issue index is below
+                             tile_limit run (a deterministic prefix of the issue order; debugging
+                             and tests)                                                              */
+  uint32_t flags;         /* T3_FLAG_*                                                               */
+} t3_problem;
+
+/*
+ * Tiles and issue order.  A chunk is cut into Mt = ceil(M/tile_m) by Wt = ceil(W/tile_n)
+ * tiles (tiles never straddle a chunk; the last row/column of tiles may be ragged),
+ * tpc = Mt*Wt tiles per chunk, T = tp*tpc tiles in all.  Issue index t in [0,T) names
+ * stage s = t / tpc (the GEMM "stage" of Sec. 2.5, one per ring step), chunk
+ * c = order[s], and inside the chunk q = t % tpc, tile row mi = q % Mt, tile column
+ * nj = q / Mt.  Workgroups are launched in issue order up to a permutation inside a
+ * stage that groups tiles sharing operands on one XCD.
+ *
+ * Supported (tile_m, tile_n): (256,128), (128,256), (128,128).
+ *
+ * Tracker state (Sec. 4.2): one caller-owned device array of t3_track_words(tp)
+ * uint32 words, cleared by t3_track_reset():
+ *   [0, tp)        counter[c]  tiles of chunk c that have landed
+ *   [tp, 2tp)      ready[c]    1 once counter[c] == tpc
+ *   [2tp, 3tp)     queue[i]    chunk ids in trigger order (forwarded chunks only, so at
+ *                              most tp-1 entries are used); 0xFFFFFFFF = empty
+ *   [3tp]          queue_len
+ *   [3tp+1, 4tp+1) claim[s]    release bookkeeping: copy units of slot s handed out
+ * Counter, ready and queue-as-a-set are deterministic; the order of queue entries
+ * follows the order in which chunks actually completed on the device.
+ */
+
+/* Ring order of `rank` and the chunk it keeps.  Host pointers: order[tp], own[1]. */
+t3_status t3_chunk_order(int32_t tp, int32_t rank, int32_t *order, int32_t *own);
+
+/* Tile shape the library would pick for this shape.  Host pointers. */
+t3_status t3_default_tile(const t3_problem *p, int32_t *tile_m, int32_t *tile_n);
+
+/* Tiles per chunk for the problem's (or the default) tile shape.  Host pointer. */
+t3_status t3_tiles_per_chunk(const t3_problem *p, int64_t *tpc);
+
+/* Issue index -> stage, chunk, tile row, tile column (host pointers).  T3_ERR_BAD_SHAPE
+   if t is outside [0, T). */
+t3_status t3_tile_of(const t3_problem *p, int64_t t, int32_t *s, int32_t *c, int32_t *mi,
+                     int32_t *nj);
+
+/* Number of uint32 words of tracker state for a ring of size tp (0 if tp < 1). */
+int64_t t3_track_words(int32_t tp);
+
+/* Clears the tracker state (a small fill kernel on `stream`).  track: device. */
+t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
+
+/*
+ * The fused path (Sec. 4.1): C = A.B is produced tile by tile in issue order and never
+ * stored on its own; each tile's epilogue forms incoming + C from R (Sec. 4.3's
+ * op-and-store, done by the compute units), then bumps the chunk's counter; the tile
+ * that completes a chunk marks it ready and, for forwarded chunks, appends it to the
+ * trigger queue, which releases the chunk into its forward slot (Sec. 4.2.2).
+ *
+ *   A    bf16 [M][lda]      read
+ *   B    bf16, see b_layout read
+ *   R    fp32 [M][ldr]      in: incoming partials.  out: incoming + C on every executed
+ *                           tile; with T3_FLAG_FWD_DIRECT only the own chunk is updated
+ *   fwd  fp32 [tp-1][M][W]  out, dense: slot s holds chunk order[s] = incoming + C.
+ *                           Default: a slot is filled (copied from R by the workgroups
+ *                           that finish after the trigger) once its chunk is complete and
+ *                           left untouched otherwise.  T3_FLAG_FWD_DIRECT: executed tiles
+ *                           are written as they finish.  May be NULL if tp == 1.
+ *   track                   tracker state, must have been reset on the same stream
+ * fp32 accumulation order is unspecified; integer outputs are exact.
+ */
+t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, float *R,
+                           float *fwd, uint32_t *track, void *stream);
+
+/* Unfused baseline, step 1: the plain sliced GEMM (Sec. 2.4).  C fp32 [M][ldc] out.
+   tp/rank/tile_limit order the tiles exactly as in the fused call; flags are ignored. */
+t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, void *stream);
+
+/* Unfused baseline, step 2: the reduce-scatter's reduction kernel (Sec. 2.3, the
+   baseline of Sec. 4.3): reads C and R, writes what t3_gemm_rs_fused would have
+   written to R / fwd, and drives the same tracker, tile by tile in the same order. */
+t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd,
+                       uint32_t *track, void *stream);
+
+const char *t3_status_string(t3_status s);
+
+/* hipError_t of the last T3_ERR_HIP on the calling thread (0 if none). */
+int32_t t3_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* T3_H */

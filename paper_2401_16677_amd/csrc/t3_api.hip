@@ -1,0 +1,298 @@
+// Host side of the C ABI declared in include/t3.h: argument validation, the launch plan
+// (ring order, tile grid, XCD grouping, release granularity) and the kernel launches.
+#include "t3.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "t3_kernels.hip"
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+
+struct TileShape {
+  int32_t m, n;
+};
+// preference order of t3_default_tile
+constexpr TileShape kTileShapes[] = {{256, 128}, {128, 256}, {128, 128}};
+constexpr int kNumTileShapes = sizeof(kTileShapes) / sizeof(kTileShapes[0]);
+constexpr int kNumXcd = 8;
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+t3_status check_shape(const t3_problem *p) {
+  if (!p) return T3_ERR_NULL;
+  if (p->M < 0 || p->N < 0 || p->K < 0 || p->tp < 1 || p->rank < 0 || p->rank >= p->tp)
+    return T3_ERR_BAD_SHAPE;
+  if (p->N % p->tp != 0) return T3_ERR_BAD_SHAPE;
+  return T3_OK;
+}
+
+bool tile_supported(int32_t tm, int32_t tn) {
+  for (int i = 0; i < kNumTileShapes; ++i)
+    if (kTileShapes[i].m == tm && kTileShapes[i].n == tn) return true;
+  return false;
+}
+
+void default_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
+  // the largest tile that still gives every compute unit two workgroups, else the smallest
+  const int64_t W = p->N / p->tp;
+  for (int i = 0; i < kNumTileShapes; ++i) {
+    const int64_t T = ceil_div(p->M, kTileShapes[i].m) * ceil_div(W, kTileShapes[i].n) * p->tp;
+    if (T >= 512) {
+      *tm = kTileShapes[i].m;
+      *tn = kTileShapes[i].n;
+      return;
+    }
+  }
+  *tm = 128;
+  *tn = 128;
+}
+
+t3_status resolve_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
+  if (p->tile_m == 0 && p->tile_n == 0) {
+    default_tile(p, tm, tn);
+    return T3_OK;
+  }
+  if (!tile_supported(p->tile_m, p->tile_n)) return T3_ERR_BAD_TILE;
+  *tm = p->tile_m;
+  *tn = p->tile_n;
+  return T3_OK;
+}
+
+inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+enum Need { kNeedAB = 1, kNeedR = 2, kNeedC = 4, kNeedFwd = 8, kNeedTrack = 16 };
+
+// Validates everything and fills the plan.  *empty is set when there is nothing to launch.
+t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B, const float *C,
+                    float *R, float *fwd, uint32_t *track, t3k::Plan *plan, int32_t *tm,
+                    int32_t *tn, bool *empty) {
+  t3_status st = check_shape(p);
+  if (st != T3_OK) return st;
+  st = resolve_tile(p, tm, tn);
+  if (st != T3_OK) return st;
+  const bool fused_like = (need & kNeedTrack) != 0;
+  const bool direct = fused_like && (p->flags & T3_FLAG_FWD_DIRECT);
+  if ((need & kNeedAB) && (!A || !B)) return T3_ERR_NULL;
+  if ((need & kNeedR) && !R) return T3_ERR_NULL;
+  if ((need & kNeedC) && !C) return T3_ERR_NULL;
+  if ((need & kNeedTrack) && !track) return T3_ERR_NULL;
+  if ((need & kNeedFwd) && p->tp > 1 && !fwd) return T3_ERR_NULL;
+  if (p->flags & ~(T3_FLAG_STEP0_STORE_ONLY | T3_FLAG_FWD_DIRECT)) return T3_ERR_UNSUPPORTED;
+
+  const int64_t W = p->N / p->tp;
+  if (need & kNeedAB) {
+    if (p->b_layout != T3_B_NK && p->b_layout != T3_B_KN) return T3_ERR_BAD_SHAPE;
+    if (p->b_layout == T3_B_KN) return T3_ERR_UNSUPPORTED;
+    if (p->lda < p->K || p->ldb < p->K) return T3_ERR_BAD_SHAPE;
+    if (p->K % 8 || p->lda % 8 || p->ldb % 8 || !aligned16(A) || !aligned16(B)) return T3_ERR_ALIGN;
+    // kernels address A and B with 32-bit element offsets
+    if ((int64_t)p->M * p->lda >= (1ll << 31) || (int64_t)p->N * p->ldb >= (1ll << 31))
+      return T3_ERR_UNSUPPORTED;
+  }
+  if (need & kNeedR) {
+    if (p->ldr < p->N) return T3_ERR_BAD_SHAPE;
+    if (p->ldr % 4 || W % 4 || !aligned16(R)) return T3_ERR_ALIGN;
+  }
+  if (need & kNeedC) {
+    if (p->ldc < p->N) return T3_ERR_BAD_SHAPE;
+    if (p->ldc % 4 || W % 4 || !aligned16(C)) return T3_ERR_ALIGN;
+  }
+  if ((need & kNeedFwd) && fwd && !aligned16(fwd)) return T3_ERR_ALIGN;
+
+  const int64_t Mt = ceil_div(p->M, *tm), Wt = ceil_div(W, *tn);
+  const int64_t tpc = Mt * Wt, T = tpc * p->tp;
+  if (T >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
+  *empty = (T == 0);
+
+  t3k::Plan &q = *plan;
+  q.A = static_cast<const uint16_t *>(A);
+  q.B = static_cast<const uint16_t *>(B);
+  q.C = C;
+  q.R = R;
+  q.fwd = fwd;
+  q.track = track;
+  q.lda = p->lda;
+  q.ldb = p->ldb;
+  q.ldr = p->ldr;
+  q.ldc = p->ldc;
+  q.limit = (p->tile_limit < 0 || p->tile_limit > T) ? T : p->tile_limit;
+  q.M = p->M;
+  q.N = p->N;
+  q.K = p->K;
+  q.P = p->tp;
+  q.rank = p->rank;
+  q.W = (int32_t)W;
+  q.own = (p->rank + p->tp - 1) % p->tp;
+  q.Mt = (int32_t)Mt;
+  q.Wt = (int32_t)Wt;
+  q.tpc = (int32_t)tpc;
+  q.flags = fused_like ? p->flags : 0u;
+  (void)direct;
+
+  // XCD grouping: split a stage's Mt x Wt tiles into 8 equal blocks, one per XCD, choosing the
+  // split whose block touches the fewest A rows + B columns.
+  q.xcd_nbm = 0;
+  q.xcd_bmk = q.xcd_bnk = 0;
+  int64_t best = -1;
+  for (int nbm = 1; nbm <= kNumXcd; nbm *= 2) {
+    const int nbn = kNumXcd / nbm;
+    if (Mt % nbm || Wt % nbn) continue;
+    const int64_t foot = (Mt / nbm) * *tm + (Wt / nbn) * *tn;
+    if (best < 0 || foot < best) {
+      best = foot;
+      q.xcd_nbm = nbm;
+      q.xcd_bmk = (int32_t)(Mt / nbm);
+      q.xcd_bnk = (int32_t)(Wt / nbn);
+    }
+  }
+
+  // release copy units of about 64 KiB
+  q.unit_rows = W > 0 ? (int32_t)(16384 / W > 0 ? 16384 / W : 1) : 1;
+  q.units_per_chunk = (int32_t)ceil_div(p->M, q.unit_rows);
+  return T3_OK;
+}
+
+t3_status launched(void) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    g_last_hip_error = (int32_t)e;
+    return T3_ERR_HIP;
+  }
+  return T3_OK;
+}
+
+template <int MODE>
+void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
+  const dim3 grid((unsigned)((int64_t)q.tpc * q.P)), block(t3k::kThreads);
+  if (tm == 256 && tn == 128)
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, MODE>), grid, block, 0, s, q);
+  else if (tm == 128 && tn == 256)
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, MODE>), grid, block, 0, s, q);
+  else
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, MODE>), grid, block, 0, s, q);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *t3_status_string(t3_status s) {
+  switch (s) {
+    case T3_OK: return "ok";
+    case T3_ERR_NULL: return "null pointer";
+    case T3_ERR_BAD_SHAPE: return "bad shape";
+    case T3_ERR_BAD_TILE: return "unsupported tile shape";
+    case T3_ERR_ALIGN: return "misaligned pointer or leading dimension";
+    case T3_ERR_UNSUPPORTED: return "unsupported request";
+    case T3_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int32_t t3_last_hip_error(void) { return g_last_hip_error; }
+
+t3_status t3_chunk_order(int32_t tp, int32_t rank, int32_t *order, int32_t *own) {
+  if (!order || !own) return T3_ERR_NULL;
+  if (tp < 1 || rank < 0 || rank >= tp) return T3_ERR_BAD_SHAPE;
+  for (int32_t s = 0; s < tp; ++s) order[s] = (rank + s) % tp;
+  *own = (rank + tp - 1) % tp;
+  return T3_OK;
+}
+
+t3_status t3_default_tile(const t3_problem *p, int32_t *tile_m, int32_t *tile_n) {
+  if (!tile_m || !tile_n) return T3_ERR_NULL;
+  const t3_status st = check_shape(p);
+  if (st != T3_OK) return st;
+  default_tile(p, tile_m, tile_n);
+  return T3_OK;
+}
+
+t3_status t3_tiles_per_chunk(const t3_problem *p, int64_t *tpc) {
+  if (!tpc) return T3_ERR_NULL;
+  t3_status st = check_shape(p);
+  if (st != T3_OK) return st;
+  int32_t tm, tn;
+  st = resolve_tile(p, &tm, &tn);
+  if (st != T3_OK) return st;
+  *tpc = ceil_div(p->M, tm) * ceil_div(p->N / p->tp, tn);
+  return T3_OK;
+}
+
+t3_status t3_tile_of(const t3_problem *p, int64_t t, int32_t *s, int32_t *c, int32_t *mi,
+                     int32_t *nj) {
+  if (!s || !c || !mi || !nj) return T3_ERR_NULL;
+  int64_t tpc;
+  const t3_status st = t3_tiles_per_chunk(p, &tpc);
+  if (st != T3_OK) return st;
+  if (t < 0 || t >= tpc * p->tp) return T3_ERR_BAD_SHAPE;
+  int32_t tm, tn;
+  resolve_tile(p, &tm, &tn);
+  const int64_t Mt = ceil_div(p->M, tm);
+  const int64_t q = t % tpc;
+  *s = (int32_t)(t / tpc);
+  *c = (p->rank + *s) % p->tp;
+  *mi = (int32_t)(q % Mt);
+  *nj = (int32_t)(q / Mt);
+  return T3_OK;
+}
+
+int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 4ll * tp + 1; }
+
+t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream) {
+  if (!track) return T3_ERR_NULL;
+  if (tp < 1 || tp > (1 << 20)) return T3_ERR_BAD_SHAPE;
+  hipLaunchKernelGGL(t3k::track_reset_kernel, dim3(1), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), track, (int)tp);
+  return launched();
+}
+
+t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, float *R,
+                           float *fwd, uint32_t *track, void *stream) {
+  t3k::Plan q;
+  int32_t tm, tn;
+  bool empty = false;
+  const t3_status st = make_plan(p, kNeedAB | kNeedR | kNeedFwd | kNeedTrack, A, B, nullptr, R,
+                                 fwd, track, &q, &tm, &tn, &empty);
+  if (st != T3_OK) return st;
+  if (empty) return T3_OK;
+  launch_gemm<t3k::kModeFused>(q, tm, tn, static_cast<hipStream_t>(stream));
+  return launched();
+}
+
+t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, void *stream) {
+  t3k::Plan q;
+  int32_t tm, tn;
+  bool empty = false;
+  const t3_status st = make_plan(p, kNeedAB | kNeedC, A, B, C, nullptr, nullptr, nullptr, &q,
+                                 &tm, &tn, &empty);
+  if (st != T3_OK) return st;
+  if (empty) return T3_OK;
+  q.R = C;   // the GEMM kernel's output pointer, addressed with ldc
+  launch_gemm<t3k::kModeGemm>(q, tm, tn, static_cast<hipStream_t>(stream));
+  return launched();
+}
+
+t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd,
+                       uint32_t *track, void *stream) {
+  t3k::Plan q;
+  int32_t tm, tn;
+  bool empty = false;
+  const t3_status st = make_plan(p, kNeedC | kNeedR | kNeedFwd | kNeedTrack, nullptr, nullptr, C,
+                                 R, fwd, track, &q, &tm, &tn, &empty);
+  if (st != T3_OK) return st;
+  if (empty) return T3_OK;
+  const dim3 grid((unsigned)((int64_t)q.tpc * q.P)), block(t3k::kThreads);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (tm == 256 && tn == 128)
+    hipLaunchKernelGGL((t3k::reduce_tile_kernel<256, 128>), grid, block, 0, s, q);
+  else if (tm == 128 && tn == 256)
+    hipLaunchKernelGGL((t3k::reduce_tile_kernel<128, 256>), grid, block, 0, s, q);
+  else
+    hipLaunchKernelGGL((t3k::reduce_tile_kernel<128, 128>), grid, block, 0, s, q);
+  return launched();
+}
+
+}  // extern "C"

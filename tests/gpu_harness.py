@@ -1,0 +1,65 @@
+"""Helpers of the GPU parity tests: put seeded host inputs on the device, call the C ABI
+through the binding, bring results back as numpy arrays."""
+import numpy as np
+import torch
+
+from paper_2401_16677_amd import binding as t3
+
+SENTINEL = -7.0
+
+
+def to_dev_bits(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+
+
+def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfused=False,
+            ldr_pad=0, lda_pad=0):
+    """One call of the fused path (or the unfused GEMM-then-reduce pair).  Returns a dict
+    with R, fwd, counter, ready, queue, queue_len (numpy) and, for unfused, C."""
+    M, K = a_bits.shape
+    N = b_bits.shape[0]
+    W = N // tp
+    dev = torch.device("cuda:0")
+    if lda_pad:
+        a_host = np.zeros((M, K + lda_pad), dtype=np.uint16)
+        a_host[:, :K] = a_bits
+        b_host = np.zeros((N, K + lda_pad), dtype=np.uint16)
+        b_host[:, :K] = b_bits
+    else:
+        a_host, b_host = a_bits, b_bits
+    A, B = to_dev_bits(a_host), to_dev_bits(b_host)
+    ldr = N + ldr_pad
+    R = torch.full((max(M, 1), ldr), 123.0, dtype=torch.float32, device=dev)
+    if M:
+        R[:M, :N] = torch.from_numpy(inc).to(dev)
+    fwd = torch.full((max(tp - 1, 1), max(M, 1), max(W, 1)), SENTINEL, dtype=torch.float32,
+                     device=dev)
+    track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+    p = t3.problem(M, N, K, tp, rank, tile[0], tile[1], lda=K + lda_pad, ldb=K + lda_pad,
+                   ldr=ldr, ldc=N, tile_limit=tile_limit, flags=flags)
+    t3.t3_track_reset(tp, track)
+    out = {}
+    if unfused:
+        C = torch.full((max(M, 1), N), 55.0, dtype=torch.float32, device=dev)
+        t3.t3_gemm(p, A, B, C)
+        t3.t3_rs_reduce(p, C, R, fwd, track)
+        torch.cuda.synchronize()
+        out["C"] = C.cpu().numpy()[:M]
+    else:
+        t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+        torch.cuda.synchronize()
+    Rh = R.cpu().numpy()
+    out["R"] = Rh[:M, :N]
+    out["R_pad"] = Rh[:M, N:]
+    out["fwd"] = fwd.cpu().numpy()[:max(tp - 1, 0), :M, :W]
+    tr = track.cpu().numpy().view(np.uint32)
+    out.update(counter=tr[0:tp], ready=tr[tp:2 * tp], queue=tr[2 * tp:3 * tp],
+               queue_len=int(tr[3 * tp]), claim=tr[3 * tp + 1:4 * tp + 1])
+    return out
+
+
+def rel_err(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    d = np.linalg.norm(np.asarray(got, dtype=np.float64) - want)
+    n = np.linalg.norm(want)
+    return d / n if n > 0 else d

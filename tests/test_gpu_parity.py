@@ -1,0 +1,168 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Integers (counters, ready flags, queue as a set, owned / forward
+partition) must be bit-exact; fp32 outputs must be within a normwise relative error of 5e-3
+(bf16 inputs, fp32 accumulation), and bit-exact on small-integer inputs where fp32
+accumulation is exact in any order."""
+import numpy as np
+import pytest
+
+from paper_2401_16677_amd import binding as t3
+from paper_2401_16677_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 5e-3          # contract
+EXPECT = 1e-4       # what fp32 accumulation should actually achieve
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "needs a GPU"
+    from tests import gpu_harness
+    return gpu_harness
+
+
+def _check_ints(got, want, tp, own):
+    assert np.array_equal(got["counter"], want["counter"])
+    assert np.array_equal(got["ready"], want["ready"])
+    assert got["queue_len"] == want["queue_len"]
+    n = want["queue_len"]
+    assert set(got["queue"][:n].tolist()) == set(want["queue"][:n].tolist())
+    assert len(set(got["queue"][:n].tolist())) == n and own not in got["queue"][:n]
+    assert np.all(got["queue"][n:] == 0xFFFFFFFF)
+
+
+def _flags(step0, direct):
+    return (t3.T3_FLAG_STEP0_STORE_ONLY if step0 else 0) | (t3.T3_FLAG_FWD_DIRECT if direct else 0)
+
+
+# several tiles per chunk, ragged M / W / K tails, every tile shape, both release modes
+EXACT_CASES = [
+    # M,   N,    K,   tp, rank, tile
+    (256, 1024, 256, 4, 0, (128, 128)),
+    (300, 800, 200, 4, 2, (128, 128)),
+    (520, 1056, 72, 2, 1, (256, 128)),
+    (260, 1200, 136, 3, 0, (128, 256)),
+    (512, 512, 64, 1, 0, (128, 128)),
+    (100, 64, 8, 8, 5, (128, 128)),
+]
+
+
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("step0", [False, True])
+@pytest.mark.parametrize("case", EXACT_CASES)
+def test_integer_inputs_bit_exact(gpu, oracle, case, step0, direct):
+    M, N, K, tp, rank, tile = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=100 + M)
+    print(f"case={case} step0={step0} direct={direct}", flush=True)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, step0_store_only=step0,
+                             fwd_direct=direct,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=_flags(step0, direct), ldr_pad=4,
+                      lda_pad=8)
+    assert np.array_equal(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"])
+    assert np.all(got["R_pad"] == 123.0)           # nothing written outside the M x N view
+    W = N // tp
+    assert np.array_equal(got["R"][:, want["own"] * W:(want["own"] + 1) * W], want["owned"])
+    _check_ints(got, want, tp, want["own"])
+
+
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("case", EXACT_CASES[:4])
+def test_unfused_baseline_bit_exact(gpu, oracle, case, direct):
+    M, N, K, tp, rank, tile = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=200 + M)
+    print(f"case={case} direct={direct}", flush=True)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=direct,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=_flags(False, direct), unfused=True)
+    assert np.array_equal(got["C"], oracle.gemm_rows(a, b).astype(np.float32))
+    assert np.array_equal(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"])
+    _check_ints(got, want, tp, want["own"])
+
+
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("limit_kind", ["zero", "one", "mid_chunk", "one_chunk", "chunk_plus",
+                                        "all_but_one"])
+def test_tile_limit_prefix_bit_exact(gpu, oracle, limit_kind, direct):
+    M, N, K, tp, rank, tile = 300, 1536, 128, 3, 1, (128, 128)
+    tpc = oracle.tiles_per_chunk(M, N, tp, *tile)
+    L = {"zero": 0, "one": 1, "mid_chunk": tpc // 2, "one_chunk": tpc, "chunk_plus": tpc + 5,
+         "all_but_one": 3 * tpc - 1}[limit_kind]
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=300)
+    print(f"limit={L} of {3 * tpc} direct={direct}", flush=True)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, tile_limit=L, fwd_direct=direct,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=_flags(False, direct), tile_limit=L)
+    assert np.array_equal(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"])
+    _check_ints(got, want, tp, want["own"])
+
+
+def test_tiny_outproj_config_float_parity(gpu, oracle):
+    w = wl.WORKLOADS["tiny_outproj"]
+    a, b, inc = wl.make_inputs(w)
+    want = oracle.fused_path(a, b, inc, w.tp, w.rank, w.tile_m, w.tile_n)
+    for flags in (0, t3.T3_FLAG_FWD_DIRECT):
+        got = gpu.run_gpu(a, b, inc, w.tp, w.rank, (w.tile_m, w.tile_n), flags=flags)
+        errs = [gpu.rel_err(got["fwd"][s], want["fwd"][s]) for s in range(w.tp - 1)]
+        own = want["own"]
+        errs.append(gpu.rel_err(got["R"][:, own * w.W:(own + 1) * w.W], want["owned"]))
+        print(f"flags={flags} normwise errors {errs}", flush=True)
+        assert max(errs) <= TOL and max(errs) <= EXPECT
+        _check_ints(got, want, w.tp, own)
+
+
+@pytest.mark.parametrize("tile", [(256, 128), (128, 256), (128, 128)])
+def test_float_multi_tile_ragged(gpu, oracle, tile):
+    M, N, K, tp, rank = 700, 2080, 328, 4, 3
+    w = wl.make_shape("ragged", M, N, K, tp, rank, *tile)
+    a, b, inc = wl.make_inputs(w, seed=77)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile)
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile)
+    assert gpu.rel_err(got["R"], want["R"]) <= EXPECT
+    assert gpu.rel_err(got["fwd"], want["fwd"]) <= EXPECT
+    assert np.abs(got["R"] - want["R"]).max() <= 1e-4 * np.abs(want["R"]).max()
+    _check_ints(got, want, tp, want["own"])
+
+
+def test_default_tile_and_k_zero_and_empty(gpu, oracle):
+    # K = 0: C is zero, the path degenerates to the partition of the incoming data
+    M, N, tp, rank = 128, 512, 4, 1
+    inc = np.arange(M * N, dtype=np.float32).reshape(M, N)
+    a = np.zeros((M, 0), dtype=np.uint16)
+    b = np.zeros((N, 0), dtype=np.uint16)
+    a_pad, b_pad = np.zeros((M, 8), np.uint16), np.zeros((N, 8), np.uint16)
+    import torch
+    from tests.gpu_harness import to_dev_bits
+    A, B = to_dev_bits(a_pad), to_dev_bits(b_pad)
+    R = torch.from_numpy(inc).cuda()
+    fwd = torch.zeros((tp - 1, M, N // tp), dtype=torch.float32, device="cuda")
+    track = torch.zeros(t3.t3_track_words(tp), dtype=torch.int32, device="cuda")
+    p = t3.problem(M, N, 0, tp, rank, lda=8, ldb=8)          # default tile
+    t3.t3_track_reset(tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+    want = oracle.fused_path(a, b, inc, tp, rank, *t3.t3_default_tile(p))
+    assert np.array_equal(R.cpu().numpy(), want["R"])
+    assert np.array_equal(fwd.cpu().numpy(), want["fwd"])
+    # M = 0: nothing runs, tracker stays clear
+    p0 = t3.problem(0, N, 64, tp, rank)
+    t3.t3_track_reset(tp, track)
+    t3.t3_gemm_rs_fused(p0, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+    tr = track.cpu().numpy()
+    assert np.all(tr[:2 * tp] == 0) and tr[3 * tp] == 0
+
+
+def test_integer_state_repeats(gpu, oracle):
+    M, N, K, tp, rank, tile = 512, 2048, 64, 8, 6, (128, 128)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=5)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile)
+    for _ in range(3):
+        got = gpu.run_gpu(a, b, inc, tp, rank, tile)
+        assert np.array_equal(got["R"], want["R"]) and np.array_equal(got["fwd"], want["fwd"])
+        _check_ints(got, want, tp, want["own"])

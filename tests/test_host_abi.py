@@ -1,0 +1,110 @@
+"""CPU-only checks of the C ABI: the library loads, exports what include/t3.h declares,
+its host-side integer logic agrees with the oracle's, and bad arguments are refused before
+anything is launched (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2401_16677_amd import binding as t3
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # an aligned non-NULL "device pointer"; refused calls never touch it
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "t3.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    declared = set(re.findall(r"\b(t3_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(t3.EXPORTS)
+    L = t3.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_problem_struct_matches_header_layout():
+    # 8 int32, 5 int64, 1 uint32 (+ padding to 8)
+    assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8
+    assert t3.T3Problem.lda.offset == 32 and t3.T3Problem.flags.offset == 72
+
+
+@pytest.mark.parametrize("tp", [1, 2, 4, 8, 16])
+def test_chunk_order_matches_oracle(oracle, tp):
+    for rank in range(tp):
+        order, own = t3.t3_chunk_order(tp, rank)
+        o_order, o_own = oracle.chunk_order(tp, rank)
+        assert order == list(o_order) and own == o_own
+
+
+@pytest.mark.parametrize("M,N,tp,rank,tm,tn", [
+    (256, 1024, 4, 0, 128, 128), (4096, 12288, 8, 3, 256, 128), (2048, 20480, 8, 7, 128, 256),
+    (300, 1000, 2, 1, 128, 128), (8192, 18432, 16, 9, 256, 128)])
+def test_tile_map_matches_oracle(oracle, M, N, tp, rank, tm, tn):
+    p = t3.problem(M, N, 64, tp, rank, tm, tn)
+    tpc = t3.t3_tiles_per_chunk(p)
+    assert tpc == oracle.tiles_per_chunk(M, N, tp, tm, tn)
+    T = tpc * tp
+    rng = np.random.default_rng(1)
+    for t in sorted(set([0, 1, tpc - 1, tpc, T - 1]) | set(rng.integers(0, T, 64).tolist())):
+        assert t3.t3_tile_of(p, int(t)) == oracle.tile_of(M, N, tp, rank, tm, tn, int(t))
+    with pytest.raises(t3.T3Error):
+        t3.t3_tile_of(p, T)
+
+
+def test_default_tile_gives_supported_shapes():
+    for (M, N, tp) in [(256, 1024, 4), (4096, 12288, 8), (2048, 20480, 8), (8192, 18432, 16),
+                       (1, 8, 2)]:
+        tm, tn = t3.t3_default_tile(t3.problem(M, N, 64, tp, 0))
+        assert (tm, tn) in [(256, 128), (128, 256), (128, 128)]
+    assert t3.t3_default_tile(t3.problem(256, 1024, 256, 4, 0)) == (128, 128)
+    assert t3.t3_default_tile(t3.problem(4096, 12288, 1536, 8, 3)) == (256, 128)
+
+
+def test_track_words():
+    assert t3.t3_track_words(8) == 33 and t3.t3_track_words(1) == 5 and t3.t3_track_words(0) == 0
+
+
+def _fused_status(p, A=FAKE, B=FAKE, R=FAKE, fwd=FAKE, track=FAKE):
+    L = t3.lib()
+    vp = ctypes.c_void_p
+    return L.t3_gemm_rs_fused(ctypes.byref(p), vp(A), vp(B), vp(R), vp(fwd), vp(track), vp(0))
+
+
+def test_bad_arguments_are_refused_before_any_launch():
+    ok = dict(M=256, N=1024, K=256, tp=4, rank=0, tile_m=128, tile_n=128)
+    L = t3.lib()
+    assert L.t3_gemm_rs_fused(None, None, None, None, None, None, None) == t3.T3_ERR_NULL
+    assert _fused_status(t3.problem(**ok), A=0) == t3.T3_ERR_NULL
+    assert _fused_status(t3.problem(**ok), fwd=0) == t3.T3_ERR_NULL
+    assert _fused_status(t3.problem(**ok), track=0) == t3.T3_ERR_NULL
+    assert _fused_status(t3.problem(**{**ok, "rank": 4})) == t3.T3_ERR_BAD_SHAPE
+    assert _fused_status(t3.problem(**{**ok, "N": 1022})) == t3.T3_ERR_BAD_SHAPE
+    assert _fused_status(t3.problem(**{**ok, "M": -1})) == t3.T3_ERR_BAD_SHAPE
+    assert _fused_status(t3.problem(**{**ok, "tp": 0})) == t3.T3_ERR_BAD_SHAPE
+    assert _fused_status(t3.problem(**ok, lda=128)) == t3.T3_ERR_BAD_SHAPE
+    assert _fused_status(t3.problem(**ok, ldr=1000)) == t3.T3_ERR_BAD_SHAPE
+    assert _fused_status(t3.problem(**{**ok, "tile_m": 96})) == t3.T3_ERR_BAD_TILE
+    assert _fused_status(t3.problem(**{**ok, "tile_n": 0})) == t3.T3_ERR_BAD_TILE
+    assert _fused_status(t3.problem(**{**ok, "K": 252})) == t3.T3_ERR_ALIGN
+    assert _fused_status(t3.problem(**ok, lda=260)) == t3.T3_ERR_ALIGN
+    assert _fused_status(t3.problem(**ok), A=FAKE + 2) == t3.T3_ERR_ALIGN
+    assert _fused_status(t3.problem(**ok), R=FAKE + 4) == t3.T3_ERR_ALIGN
+    assert _fused_status(t3.problem(**{**ok, "N": 1016})) == t3.T3_ERR_ALIGN   # W = 254
+    assert _fused_status(t3.problem(**ok, b_layout=t3.T3_B_KN)) == t3.T3_ERR_UNSUPPORTED
+    assert _fused_status(t3.problem(**ok, flags=8)) == t3.T3_ERR_UNSUPPORTED
+    assert _fused_status(t3.problem(**ok, b_layout=7)) == t3.T3_ERR_BAD_SHAPE
+    # empty problems are fine and launch nothing
+    assert _fused_status(t3.problem(**{**ok, "M": 0})) == t3.T3_OK
+    assert _fused_status(t3.problem(**{**ok, "N": 0})) == t3.T3_OK
+    vp = ctypes.c_void_p
+    p = t3.problem(**ok)
+    assert L.t3_gemm(ctypes.byref(p), vp(FAKE), vp(FAKE), vp(0), vp(0)) == t3.T3_ERR_NULL
+    assert L.t3_rs_reduce(ctypes.byref(p), vp(0), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
+        t3.T3_ERR_NULL
+    assert L.t3_track_reset(4, vp(0), vp(0)) == t3.T3_ERR_NULL
+    assert L.t3_track_reset(0, vp(FAKE), vp(0)) == t3.T3_ERR_BAD_SHAPE
+    assert t3.status_string(t3.T3_ERR_BAD_TILE) == "unsupported tile shape"
+    with pytest.raises(t3.T3Error):
+        t3.t3_chunk_order(4, 5)
