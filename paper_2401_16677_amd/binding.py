@@ -48,6 +48,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(
                 f"{LIB_PATH} is not built: run `python -m paper_2401_16677_amd.build`")
+        # The library must bind to the HIP runtime that owns the caller's device memory and
+        # streams.  PyTorch ships its own copy, so it is loaded first and libt3.so's
+        # dependency on libamdhip64 resolves to that one.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         pp = ctypes.POINTER(T3Problem)
