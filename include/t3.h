@@ -90,9 +90,12 @@ typedef struct {
  *   [2tp, 3tp)     queue[i]    chunk ids in trigger order (forwarded chunks only, so at
  *                              most tp-1 entries are used); 0xFFFFFFFF = empty
  *   [3tp]          queue_len
- *   [3tp+1, 4tp+1) claim[s]    release bookkeeping: copy units of slot s handed out
+ *   [3tp+1]        error       0, or 1 if a release workgroup gave up waiting for a chunk
+ *                              (cannot happen in a launch that ran to completion)
  * Counter, ready and queue-as-a-set are deterministic; the order of queue entries
- * follows the order in which chunks actually completed on the device.
+ * follows the order in which chunks actually completed on the device.  A tile's results are
+ * visible to the whole device before it is counted, so a consumer that observes ready[c] (with
+ * an acquiring load) may read chunk c.
  */
 
 /* Ring order of `rank` and the chunk it keeps.  Host pointers: order[tp], own[1]. */
@@ -127,9 +130,9 @@ t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
  *   R    fp32 [M][ldr]      in: incoming partials.  out: incoming + C on every executed
  *                           tile; with T3_FLAG_FWD_DIRECT only the own chunk is updated
  *   fwd  fp32 [tp-1][M][W]  out, dense: slot s holds chunk order[s] = incoming + C.
- *                           Default: a slot is filled (copied from R by the workgroups
- *                           that finish after the trigger) once its chunk is complete and
- *                           left untouched otherwise.  T3_FLAG_FWD_DIRECT: executed tiles
+ *                           Default: a slot is filled once its chunk is complete (copied
+ *                           from R by release workgroups of the same launch, which wait on
+ *                           the chunk's ready flag) and left untouched otherwise.  T3_FLAG_FWD_DIRECT: executed tiles
  *                           are written as they finish.  May be NULL if tp == 1.
  *   track                   tracker state, must have been reset on the same stream
  * fp32 accumulation order is unspecified; integer outputs are exact.

@@ -171,6 +171,6 @@ def t3_rs_reduce(p, C, R, fwd, track, stream=None):
 
 
 def track_views(track, tp):
-    """Slices of a tracker-state tensor: counter, ready, queue, queue_len, claim."""
+    """Slices of a tracker-state tensor: counter, ready, queue, queue_len, error."""
     return {"counter": track[0:tp], "ready": track[tp:2 * tp], "queue": track[2 * tp:3 * tp],
-            "queue_len": track[3 * tp:3 * tp + 1], "claim": track[3 * tp + 1:4 * tp + 1]}
+            "queue_len": track[3 * tp:3 * tp + 1], "error": track[3 * tp + 1:3 * tp + 2]}

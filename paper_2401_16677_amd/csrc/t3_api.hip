@@ -130,7 +130,6 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.Wt = (int32_t)Wt;
   q.tpc = (int32_t)tpc;
   q.flags = fused_like ? p->flags : 0u;
-  (void)direct;
 
   // XCD grouping: split a stage's Mt x Wt tiles into 8 equal blocks, one per XCD, choosing the
   // split whose block touches the fewest A rows + B columns.
@@ -149,9 +148,14 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
     }
   }
 
-  // release copy units of about 64 KiB
-  q.unit_rows = W > 0 ? (int32_t)(16384 / W > 0 ? 16384 / W : 1) : 1;
-  q.units_per_chunk = (int32_t)ceil_div(p->M, q.unit_rows);
+  // Release workgroups (default release mode only): `agents` per forwarded chunk, placed in
+  // the grid `lag` stages after the chunk's own tiles, far enough that those tiles have been
+  // dispatched and are mostly finished when the release workgroups start.
+  q.agents = (fused_like && !direct && p->tp > 1) ? T3_AGENTS : 0;
+  q.lag = (int32_t)(ceil_div(512, tpc > 0 ? tpc : 1) + 1);
+  if (q.lag > p->tp) q.lag = p->tp;
+  q.rows_per_agent = q.agents ? (int32_t)ceil_div(p->M, q.agents) : 0;
+  if ((T + (int64_t)q.agents * (p->tp - 1)) >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
   return T3_OK;
 }
 
@@ -164,9 +168,13 @@ t3_status launched(void) {
   return T3_OK;
 }
 
+inline unsigned grid_size(const t3k::Plan &q) {
+  return (unsigned)((int64_t)q.tpc * q.P + (int64_t)q.agents * (q.P - 1));
+}
+
 template <int MODE>
 void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
-  const dim3 grid((unsigned)((int64_t)q.tpc * q.P)), block(t3k::kThreads);
+  const dim3 grid(grid_size(q)), block(t3k::kThreads);
   if (tm == 256 && tn == 128)
     hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, MODE>), grid, block, 0, s, q);
   else if (tm == 128 && tn == 256)
@@ -239,7 +247,7 @@ t3_status t3_tile_of(const t3_problem *p, int64_t t, int32_t *s, int32_t *c, int
   return T3_OK;
 }
 
-int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 4ll * tp + 1; }
+int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 3ll * tp + 2; }
 
 t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream) {
   if (!track) return T3_ERR_NULL;
@@ -284,7 +292,7 @@ t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd
                                  R, fwd, track, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
-  const dim3 grid((unsigned)((int64_t)q.tpc * q.P)), block(t3k::kThreads);
+  const dim3 grid(grid_size(q)), block(t3k::kThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (tm == 256 && tn == 128)
     hipLaunchKernelGGL((t3k::reduce_tile_kernel<256, 128>), grid, block, 0, s, q);

@@ -1,11 +1,16 @@
 // Device code of the fused sliced-GEMM + reduce-scatter-reduction path for gfx950 (CDNA4).
 //
-// One workgroup (256 threads = 4 wavefronts of 64, arranged 2 x 2) produces one
-// BM x BN output tile with v_mfma_f32_32x32x16_bf16.  A and B K-slabs of 64 bf16 are
-// staged through LDS in an XOR-swizzled layout; the next slab is prefetched into
-// registers while the current one is multiplied.  Two workgroups fit on a compute unit,
-// so one workgroup's epilogue traffic (the reduction with the incoming partial, Sec. 4.3
-// of the T3 paper) runs under the other's matrix work.
+// One workgroup (256 threads = 4 wavefronts of 64, arranged 2 x 2) produces one BM x BN
+// output tile with v_mfma_f32_32x32x16_bf16.  K-slabs of 32 bf16 of A and B are copied
+// global -> LDS without passing through registers (global_load_lds_dwordx4) into a ring of
+// three stages, two slabs ahead of the one being multiplied; LDS rows are XOR-swizzled so
+// that the MFMA operand reads are bank-conflict free.  Two workgroups fit on a compute unit:
+// while one waits on memory (its incoming partial, its stores) the other keeps the matrix
+// cores busy.
+//
+// The reduction of Sec. 4.3 of the T3 paper (op-and-store into the buffer that also receives
+// the upstream partial) is done by starting the accumulators from the incoming partial, so a
+// tile is read once at its start and written once at its end.
 //
 // Included by t3_api.hip only.
 #pragma once
@@ -13,21 +18,36 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef T3_AGENTS
+#define T3_AGENTS 32          // release workgroups per forwarded chunk (multiple of 8)
+#endif
+
 namespace t3k {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *global_void_ptr;
 
 constexpr int kThreads = 256;
-constexpr int kBK = 64;               // bf16 elements of K per slab: one 128-byte LDS row
-constexpr int kChunksPerRow = 8;      // 16-byte chunks in an LDS row
+constexpr int kBK = 32;               // bf16 elements of K per slab
+constexpr int kRowBytes = 64;         // one LDS row = one tile row of a slab
+constexpr int kStages = 3;
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
+constexpr int kSpinLimit = 1 << 22;   // polls of a release workgroup before it gives up
 
 constexpr uint32_t kFlagStep0StoreOnly = 1u;
 constexpr uint32_t kFlagFwdDirect = 2u;
 
 enum Mode { kModeGemm = 0, kModeFused = 1 };
+enum Role { kRoleNone = 0, kRoleTile = 1, kRoleRelease = 2 };
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14)
+constexpr int kWaitVm0 = 0x0F70;
+constexpr int kWaitLgkm0 = 0xF0FF;    // and-mask that turns a wait into "... and lgkmcnt(0)"
+constexpr int kWaitAll = 0;
+__host__ __device__ constexpr int wait_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 // Everything a kernel needs, passed by value.
 struct Plan {
@@ -42,7 +62,7 @@ struct Plan {
   int32_t M, N, K, P, rank, W, own;
   int32_t Mt, Wt, tpc;
   int32_t xcd_nbm, xcd_bmk, xcd_bnk;   // XCD grouping of a stage's tiles; xcd_nbm == 0: none
-  int32_t unit_rows, units_per_chunk;  // release copy granularity
+  int32_t agents, lag, rows_per_agent; // release workgroups per chunk, their lag in stages
   uint32_t flags;
 };
 
@@ -50,13 +70,17 @@ struct Tile {
   int s, c, mi, nj;
 };
 
-// blockIdx -> issue index -> tile.  Workgroups are dealt round-robin to the 8 XCDs, so
-// inside a stage workgroup j lands on XCD j % 8; that XCD gets a compact block of
+// Tracker state layout (uint32 words): counter[P] ready[P] queue[P] queue_len error.
+__device__ inline uint32_t *trk_counter(const Plan &p) { return p.track; }
+__device__ inline uint32_t *trk_ready(const Plan &p) { return p.track + p.P; }
+__device__ inline uint32_t *trk_queue(const Plan &p) { return p.track + 2 * p.P; }
+__device__ inline uint32_t *trk_queue_len(const Plan &p) { return p.track + 3 * p.P; }
+__device__ inline uint32_t *trk_error(const Plan &p) { return p.track + 3 * p.P + 1; }
+
+// Index j of a tile inside its stage -> tile.  Workgroups are dealt round-robin to the 8 XCDs,
+// so workgroup j of a stage lands on XCD j % 8; that XCD gets a compact block of
 // xcd_bmk x xcd_bnk tiles which share A rows and B columns in its L2.
-__device__ inline bool decode_tile(const Plan &p, Tile &tl) {
-  const int b = blockIdx.x;
-  const int s = b / p.tpc;
-  const int j = b - s * p.tpc;
+__device__ inline bool decode_tile(const Plan &p, int s, int j, Tile &tl) {
   int mi, nj;
   if (p.xcd_nbm) {
     const int x = j & 7, i = j >> 3;
@@ -67,7 +91,7 @@ __device__ inline bool decode_tile(const Plan &p, Tile &tl) {
     mi = j % p.Mt;
     nj = j / p.Mt;
   }
-  const int64_t t = (int64_t)s * p.tpc + (int64_t)nj * p.Mt + mi;
+  const int64_t t = (int64_t)s * p.tpc + (int64_t)nj * p.Mt + mi;   // issue index
   int c = p.rank + s;
   if (c >= p.P) c -= p.P;
   tl.s = s;
@@ -77,108 +101,139 @@ __device__ inline bool decode_tile(const Plan &p, Tile &tl) {
   return t < p.limit;
 }
 
-// LDS row r keeps its 16-byte chunk k at position k ^ swz(r): 16 consecutive rows read
-// at one k land in 16 different bank groups.
-__device__ inline int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+// Grid layout: the tiles of stage 0, 1, ... in order; after the tiles of stage s come the
+// `agents` release workgroups of forward slot s - lag (a chunk whose tiles were all dispatched
+// at least `lag` stages earlier); slots not served that way follow the last stage.
+__device__ inline int decode_block(const Plan &p, Tile &tl, int &slot, int &agent) {
+  const int b = blockIdx.x;
+  int base = 0;
+  for (int s = 0; s < p.P; ++s) {
+    if (b < base + p.tpc) return decode_tile(p, s, b - base, tl) ? kRoleTile : kRoleNone;
+    base += p.tpc;
+    const int sl = s - p.lag;
+    if (p.agents && sl >= 0 && sl <= p.P - 2) {
+      if (b < base + p.agents) {
+        slot = sl;
+        agent = b - base;
+        return kRoleRelease;
+      }
+      base += p.agents;
+    }
+  }
+  if (!p.agents) return kRoleNone;
+  const int rem = b - base;
+  slot = max(0, p.P - p.lag) + rem / p.agents;
+  agent = rem % p.agents;
+  return slot <= p.P - 2 ? kRoleRelease : kRoleNone;
+}
+
+// Stores that are visible to every XCD once acknowledged: agent scope, i.e. the sc1 bit, which
+// writes through the issuing XCD's L2.  (Plain and non-temporal stores stay in that L2 until a
+// release fence writes the whole cache back.)
+__device__ inline void store_agent(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void store_agent(f32x4 *p, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
 
 // ---------------------------------------------------------------------------------------------
-// Track & trigger (Sec. 4.2), then release of triggered chunks into their forward slots.
-// Called by all threads of a workgroup after the tile's stores have been issued.
-__device__ inline void track_and_release(const Plan &p, int c, uint32_t *sh) {
-  const int tid = threadIdx.x;
-  uint32_t *counter = p.track;
-  uint32_t *ready = counter + p.P;
-  uint32_t *queue = ready + p.P;
-  uint32_t *queue_len = queue + p.P;
-  uint32_t *claim = queue_len + 1;
-
-  __threadfence();      // this thread's tile stores are visible device-wide ...
-  __syncthreads();      // ... for every thread of the workgroup, before the tile is counted
-  if (tid == 0) {
-    const uint32_t old =
-        __hip_atomic_fetch_add(&counter[c], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+// Track & trigger (Sec. 4.2).  Called by all threads of a workgroup after the tile's stores
+// have been issued.  Tile results are written with agent-scope stores; once they have been
+// acknowledged (vmcnt == 0 in every wavefront, then the barrier) the tile is counted.  A
+// device-scope release fence instead would write back the whole L2 for every tile and costs
+// several times the reduction itself.
+__device__ inline void track_tile(const Plan &p, int c) {
+  __builtin_amdgcn_s_waitcnt(kWaitAll);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t old = __hip_atomic_fetch_add(&trk_counter(p)[c], 1u, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1u == (uint32_t)p.tpc) {   // the landing that reaches the threshold triggers
       if (c != p.own) {
-        const uint32_t pos =
-            __hip_atomic_fetch_add(queue_len, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&queue[pos], (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t pos = __hip_atomic_fetch_add(trk_queue_len(p), 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&trk_queue(p)[pos], (uint32_t)c, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
       }
-      __hip_atomic_store(&ready[c], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&trk_ready(p)[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-  if ((p.flags & kFlagFwdDirect) || p.P == 1) return;
+}
 
-  // Release: every workgroup that finishes a tile hands out and copies pieces ("units" of
-  // unit_rows rows) of the chunks that are ready, until none are left.  The workgroup that
-  // triggered a chunk stays until all of its units are handed out, and a unit's claimer
-  // finishes it before exiting, so every triggered chunk is in its slot when the grid ends.
+// Release of a triggered chunk into its forward slot (the DMA of Sec. 4.2.2): workgroup `agent`
+// of `agents` waits for the chunk's ready flag and copies its share of rows.  Every tile of the
+// chunk was dispatched before this workgroup (lower block index), so the wait ends; should it
+// not (a broken launch), the workgroup gives up after kSpinLimit polls and raises the error word.
+__device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_t *sh) {
+  if ((int64_t)(slot + 1) * p.tpc > p.limit) return;   // this chunk will not complete
+  int c = p.rank + slot;
+  if (c >= p.P) c -= p.P;
+  if (threadIdx.x == 0) {
+    int spins = 0;
+    while (__hip_atomic_load(&trk_ready(p)[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
+           ++spins < kSpinLimit)
+      __builtin_amdgcn_s_sleep(16);
+    const uint32_t ok = spins < kSpinLimit;
+    if (!ok) __hip_atomic_fetch_or(trk_error(p), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *sh = ok;
+  }
+  __syncthreads();
+  if (!*sh) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of R
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int W4 = p.W >> 2;
-  for (int s2 = 0; s2 < p.P - 1; ++s2) {
-    int c2 = p.rank + s2;
-    if (c2 >= p.P) c2 -= p.P;
-    for (;;) {
-      __syncthreads();
-      if (tid == 0) {
-        uint32_t u = kEmpty;
-        if (__hip_atomic_load(&ready[c2], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) &&
-            __hip_atomic_load(&claim[s2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
-                (uint32_t)p.units_per_chunk)
-          u = __hip_atomic_fetch_add(&claim[s2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *sh = u;
-      }
-      __syncthreads();
-      const uint32_t u = *sh;
-      if (u >= (uint32_t)p.units_per_chunk) break;
-      __threadfence();    // other workgroups' sums, published before ready[c2], are visible here
-      const int r0 = (int)u * p.unit_rows;
-      const int nr = min(p.unit_rows, p.M - r0);
-      const float *src = p.R + (int64_t)r0 * p.ldr + (int64_t)c2 * p.W;
-      float *dst = p.fwd + ((int64_t)s2 * p.M + r0) * p.W;
-      const int total = nr * W4;
-      for (int e = tid; e < total; e += kThreads) {
-        const int rr = e / W4, cc = e - rr * W4;
-        const f32x4 v = __builtin_nontemporal_load((const f32x4 *)(src + (int64_t)rr * p.ldr) + cc);
-        __builtin_nontemporal_store(v, (f32x4 *)(dst + (int64_t)rr * p.W) + cc);
-      }
+  const int r_end = min(p.M, (agent + 1) * p.rows_per_agent);
+  for (int r = agent * p.rows_per_agent + wave; r < r_end; r += kThreads / 64) {
+    const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
+    f32x4 *dst = (f32x4 *)(p.fwd + ((int64_t)slot * p.M + r) * p.W);
+    for (int c0 = lane; c0 < W4; c0 += 4 * 64) {
+      f32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * 64 < W4) v[u] = __builtin_nontemporal_load(src + c0 + u * 64);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * 64 < W4) __builtin_nontemporal_store(v[u], dst + c0 + u * 64);
     }
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Global -> register loads of one K-slab: ROWS rows of 64 bf16, 16 bytes per thread per pass.
-template <int ROWS>
-__device__ inline void load_slab(uint4 (&regs)[ROWS * kChunksPerRow / kThreads],
-                                 const uint16_t *base, const uint32_t (&off)[ROWS * kChunksPerRow / kThreads],
-                                 int k0, int K, int kc_local) {
-  constexpr int N = ROWS * kChunksPerRow / kThreads;
-  if (k0 + kBK <= K) {
-#pragma unroll
-    for (int i = 0; i < N; ++i)
-      regs[i] = *(const uint4 *)(base + k0 + off[i]);
-  } else {   // ragged last slab: chunks past K are zeros (K is a multiple of 8)
-    const bool in = k0 + kc_local < K;
-#pragma unroll
-    for (int i = 0; i < N; ++i)
-      regs[i] = in ? *(const uint4 *)(base + k0 + off[i]) : make_uint4(0, 0, 0, 0);
-  }
-}
+// LDS layout of one stage: BM rows of A then BN rows of B, 64 bytes (4 chunks of 16) per row.
+// Row r keeps chunk k at position k ^ swz(r), which makes both the 1-KiB linear writes of the
+// global->LDS copies and the MFMA operand reads (consecutive rows, one k) conflict free.
+__device__ inline int swz(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
+
+// sched_group_barrier masks
+constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
 
 template <int BM, int BN, int MODE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void gemm_tile_kernel(const Plan p) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
+void gemm_tile_kernel(const Plan p) {
   constexpr int WM = BM / 2, WN = BN / 2;       // wavefront tile
   constexpr int FM = WM / 32, FN = WN / 32;     // 32x32 MFMA blocks per wavefront
-  constexpr int NA = BM * kChunksPerRow / kThreads;
-  constexpr int NB = BN * kChunksPerRow / kThreads;
+  constexpr int NA = BM / 64, NB = BN / 64;     // global->LDS copies per wavefront per slab
+  constexpr int NL = NA + NB;
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  constexpr int kBOff = BM * kRowBytes;
 
-  __shared__ uint4 lds[(BM + BN) * kChunksPerRow];
+  __shared__ __attribute__((aligned(1024))) char lds[kStages * kStageBytes];
   __shared__ uint32_t sh_word;
 
   Tile tl;
-  if (!decode_tile(p, tl)) return;
+  int slot = 0, agent = 0;
+  const int role = decode_block(p, tl, slot, agent);
+  if (role == kRoleNone) return;
+  if (role == kRoleRelease) {
+    if (MODE == kModeFused) release_chunk(p, slot, agent, &sh_word);
+    return;
+  }
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
   const int m0 = tl.mi * BM;
@@ -186,120 +241,202 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
   const int col_hi = col_lo + p.W;
   const int n0 = col_lo + tl.nj * BN;
 
-  // per-thread global offsets (in elements) of its 16-byte chunks; rows clamped into range
-  const int ld_row = tid >> 3, ld_chunk = tid & 7;
-  uint32_t offA[NA], offB[NB];
+  // ---- global -> LDS copy addressing.  Copy q of this wavefront fills 16 LDS rows (1 KiB):
+  // lane l lands in row l/4, position l%4, so it must fetch chunk (l%4) ^ swz(row).
+  const int cp_row = lane >> 2;
+  const int cp_chunk = (lane & 3) ^ swz(cp_row);
+  uint32_t offA[NA], offB[NB];                   // byte offsets, rows clamped into range
 #pragma unroll
-  for (int i = 0; i < NA; ++i)
-    offA[i] = (uint32_t)(min(m0 + ld_row + i * 32, p.M - 1) * p.lda + ld_chunk * 8);
+  for (int q = 0; q < NA; ++q)
+    offA[q] = (uint32_t)((min(m0 + wave * (BM / 4) + q * 16 + cp_row, p.M - 1) * p.lda + cp_chunk * 8) * 2);
 #pragma unroll
-  for (int i = 0; i < NB; ++i)
-    offB[i] = (uint32_t)(min(n0 + ld_row + i * 32, col_hi - 1) * p.ldb + ld_chunk * 8);
-  const int st_slot = ld_row * kChunksPerRow + (ld_chunk ^ swz(ld_row));   // rows +32 keep swz
+  for (int q = 0; q < NB; ++q)
+    offB[q] = (uint32_t)((min(n0 + wave * (BN / 4) + q * 16 + cp_row, col_hi - 1) * p.ldb + cp_chunk * 8) * 2);
+  const int ldsA_w = wave * (BM / 4) * kRowBytes;            // this wavefront's rows, stage 0
+  const int ldsB_w = kBOff + wave * (BN / 4) * kRowBytes;
 
+  // The copies are issued as inline assembly: the compiler would otherwise wait for every
+  // outstanding global->LDS copy (vmcnt(0)) before any LDS read, which defeats the prefetch.
+  // Waits for them are therefore explicit (s_waitcnt below).
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
+  auto issue_slab = [&](int kt, int stage) {
+    const char *a = (const char *)p.A + (int64_t)kt * (kBK * 2);
+    const char *b = (const char *)p.B + (int64_t)kt * (kBK * 2);
+    const uint32_t dst = lds_base + stage * kStageBytes;
+#pragma unroll
+    for (int q = 0; q < NA; ++q)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(dst + ldsA_w + q * 1024), "v"(offA[q]), "s"(a)
+                   : "memory");
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(dst + ldsB_w + q * 1024), "v"(offB[q]), "s"(b)
+                   : "memory");
+  };
+
+  // ---- MFMA operand addressing: lane reads row (lane & 31) of a 32-row block, k-chunk
+  // 2*kk + (lane >> 5).
+  const int fr = lane & 31, fh = lane >> 5, fs = swz(fr);
+  const int pos0 = ((0 + fh) ^ fs) * 16, pos1 = ((2 + fh) ^ fs) * 16;
+  const int fragA0 = (wm * WM + fr) * kRowBytes + pos0, fragA1 = (wm * WM + fr) * kRowBytes + pos1;
+  const int fragB0 = kBOff + (wn * WN + fr) * kRowBytes + pos0;
+  const int fragB1 = kBOff + (wn * WN + fr) * kRowBytes + pos1;
+
+  const int nkf = p.K / kBK;                     // full slabs
+  const int ktail = p.K - nkf * kBK;             // 0, 8, 16 or 24 leftover elements of K
+
+  // Two slabs are always in flight.  Past the last slab the copies are repeated into stages
+  // nobody reads any more, so every wait below is for the same number of younger copies.
+  if (nkf > 0) issue_slab(0, 0);
+
+  // ---- accumulators start from the incoming partial (fused) or zero.
+  // Element 4*g + e of block (i, j) is row 8*g + 4*(lane>>5) + e, column lane & 31 of the
+  // block: per register, 32 lanes cover 128 contiguous bytes of one output row.  All lanes
+  // share one 32-bit offset; the row of each register is folded into a scalar base.
+  const bool store_only = (MODE == kModeGemm) || ((p.flags & kFlagStep0StoreOnly) && tl.s == 0);
+  const bool to_fwd = (MODE == kModeFused) && (p.flags & kFlagFwdDirect) && tl.c != p.own;
+  const int rw0 = m0 + wm * WM, cw0 = n0 + wn * WN;          // wavefront tile origin (uniform)
+  const bool full = (rw0 + WM <= p.M) && (cw0 + WN <= col_hi);
+  const int64_t ld_in = p.ldr;
+  const uint32_t in_voff = (uint32_t)((4 * fh * ld_in + fr) * 4);
   f32x16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 16; ++e) {
+        float v = 0.f;
+        if (MODE == kModeFused && !store_only) {
+          const int rr = i * 32 + 8 * (e >> 2) + (e & 3);         // + 4*fh per lane
+          const char *sb = (const char *)(p.R + (int64_t)(rw0 + rr) * ld_in + cw0 + j * 32);
+          if (full || (rw0 + rr + 4 * fh < p.M && cw0 + j * 32 + fr < col_hi))
+            v = __builtin_nontemporal_load((const float *)(sb + in_voff));
+        }
+        acc[i][j][e] = v;
+      }
 
-  uint4 ra[NA], rb[NB];
-  const int nk = (p.K + kBK - 1) / kBK;
-  if (nk > 0) {
-    load_slab<BM>(ra, p.A, offA, 0, p.K, ld_chunk * 8);
-    load_slab<BN>(rb, p.B, offB, 0, p.K, ld_chunk * 8);
+  if (nkf > 0) issue_slab(min(1, nkf - 1), 1);
+
+  bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
+#define T3_READ_FRAGS(fa, fb, fragA, fragB, stage_off)                                   \
+  {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i)                                       \
+      fa[i] = *(const bf16x8 *)(lds + (stage_off) + fragA + i * 32 * kRowBytes);         \
+    _Pragma("unroll") for (int j = 0; j < FN; ++j)                                       \
+      fb[j] = *(const bf16x8 *)(lds + (stage_off) + fragB + j * 32 * kRowBytes);         \
+  }
+#define T3_MFMA_STEP(fa, fb)                                                             \
+  {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i)                                       \
+      _Pragma("unroll") for (int j = 0; j < FN; ++j)                                     \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0); \
   }
 
-  // fragment read addressing: lane reads row (lane & 31) of a 32-row block, chunk 2*kk + (lane>>5)
-  const int fr = lane & 31, fh = lane >> 5, fs = swz(fr);
-  const uint4 *ldsA = lds + (wm * WM + fr) * kChunksPerRow;
-  const uint4 *ldsB = lds + (BM + wn * WN + fr) * kChunksPerRow;
-
-  for (int kt = 0; kt < nk; ++kt) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i) lds[st_slot + i * 32 * kChunksPerRow] = ra[i];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) lds[BM * kChunksPerRow + st_slot + i * 32 * kChunksPerRow] = rb[i];
-    __syncthreads();
-    if (kt + 1 < nk) {
-      load_slab<BM>(ra, p.A, offA, (kt + 1) * kBK, p.K, ld_chunk * 8);
-      load_slab<BN>(rb, p.B, offB, (kt + 1) * kBK, p.K, ld_chunk * 8);
+  // ---- main loop: slab kt is multiplied while slabs kt+1 and kt+2 are in flight.  The second
+  // half of a slab's products is issued after the next barrier, under the next slab's LDS reads.
+  if (nkf > 0) {
+    __builtin_amdgcn_s_waitcnt(wait_vm(NL));       // slab 0 (and the incoming partial) landed
+    __builtin_amdgcn_s_barrier();
+    issue_slab(min(2, nkf - 1), 2);
+    T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, 0);
+    T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, 0);
+    T3_MFMA_STEP(fa0, fb0);
+    int stage = 1;
+    for (int kt = 1; kt < nkf; ++kt) {
+      const int so = stage * kStageBytes;
+      asm volatile("" ::: "memory");               // LDS reads above stay above the barrier
+      __builtin_amdgcn_s_waitcnt(wait_vm(NL) & kWaitLgkm0);   // own copies of slab kt landed, own LDS reads done
+      __builtin_amdgcn_s_barrier();                // everyone's; all are done with the stage refilled next
+      issue_slab(min(kt + 2, nkf - 1), stage >= 1 ? stage - 1 : 2);
+      T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, so);
+      T3_MFMA_STEP(fa1, fb1);                      // second half of slab kt-1
+      T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, so);
+      T3_MFMA_STEP(fa0, fb0);
+      __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, NL, 0);
+      __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FM + FN, 0);
+      __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
+      __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FM + FN, 0);
+      __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
+      stage = stage == 2 ? 0 : stage + 1;
     }
-#pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      const int pos = (2 * kk + fh) ^ fs;
-      bf16x8 af[FM], bf[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-        af[i] = __builtin_bit_cast(bf16x8, ldsA[i * 32 * kChunksPerRow + pos]);
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        bf[j] = __builtin_bit_cast(bf16x8, ldsB[j * 32 * kChunksPerRow + pos]);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();
+    T3_MFMA_STEP(fa1, fb1);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies
   }
+  asm volatile("" ::: "memory");
 
-  // Epilogue.  Accumulator element 4*g + e of block (i, j) is row 8*g + 4*(lane>>5) + e,
-  // column lane & 31 of the block: per register, 32 lanes cover 128 contiguous bytes of a row.
-  const bool store_only = (MODE == kModeGemm) ||
-                          ((p.flags & kFlagStep0StoreOnly) && tl.s == 0);
-  const bool to_fwd = (MODE == kModeFused) && (p.flags & kFlagFwdDirect) && tl.c != p.own;
-  const int64_t ld_in = (MODE == kModeGemm) ? p.ldc : p.ldr;
-  float *out_base;
+  if (ktail) {
+    // ragged end of K: through registers, chunks past K zeroed, into stage 0
+    __syncthreads();
+    const int64_t kb = (int64_t)nkf * (kBK * 2);
+    const bool in = cp_chunk * 8 < ktail;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+      uint4 v = zero;
+      if (in) v = *(const uint4 *)((const char *)p.A + kb + offA[q]);
+      *(uint4 *)(lds + ldsA_w + q * 1024 + lane * 16) = v;
+    }
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      uint4 v = zero;
+      if (in) v = *(const uint4 *)((const char *)p.B + kb + offB[q]);
+      *(uint4 *)(lds + ldsB_w + q * 1024 + lane * 16) = v;
+    }
+    __syncthreads();
+    T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, 0);
+    T3_MFMA_STEP(fa0, fb0);
+    if (ktail > 16) {
+      T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, 0);
+      T3_MFMA_STEP(fa1, fb1);
+    }
+  }
+#undef T3_READ_FRAGS
+#undef T3_MFMA_STEP
+
+  // ---- epilogue: one agent-scope store per accumulator register
+  float *out_base;        // origin of this wavefront's tile in the output
   int64_t ld_out;
-  int col_shift;
   if (to_fwd) {
-    out_base = p.fwd + (int64_t)tl.s * p.M * p.W;
     ld_out = p.W;
-    col_shift = col_lo;
+    out_base = p.fwd + ((int64_t)tl.s * p.M + rw0) * p.W + (cw0 - col_lo);
   } else {
-    out_base = p.R;
-    ld_out = ld_in;
-    col_shift = 0;
+    ld_out = (MODE == kModeGemm) ? p.ldc : p.ldr;
+    out_base = p.R + (int64_t)rw0 * ld_out + cw0;
   }
+  const uint32_t out_voff = (uint32_t)((4 * fh * ld_out + fr) * 4);
 #pragma unroll
-  for (int i = 0; i < FM; ++i) {
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int col = n0 + wn * WN + j * 32 + fr;
-      const int row_b = m0 + wm * WM + i * 32 + 4 * fh;
-      const bool col_ok = col < col_hi;
-      float inc[16];
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int row = row_b + 8 * (e >> 2) + (e & 3);
-        inc[e] = 0.f;
-        if (!store_only && col_ok && row < p.M)
-          inc[e] = __builtin_nontemporal_load(p.R + (int64_t)row * ld_in + col);
+        const int rr = i * 32 + 8 * (e >> 2) + (e & 3);
+        char *sb = (char *)(out_base + (int64_t)rr * ld_out + j * 32);
+        if (full || (rw0 + rr + 4 * fh < p.M && cw0 + j * 32 + fr < col_hi))
+          store_agent((float *)(sb + out_voff), acc[i][j][e]);
       }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = row_b + 8 * (e >> 2) + (e & 3);
-        if (col_ok && row < p.M)
-          __builtin_nontemporal_store(inc[e] + acc[i][j][e],
-                                      out_base + (int64_t)row * ld_out + (col - col_shift));
-      }
-    }
-  }
 
-  if (MODE == kModeFused) track_and_release(p, tl.c, &sh_word);
+  if (MODE == kModeFused) track_tile(p, tl.c);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Unfused baseline, second kernel: the reduce-scatter's reduction (Sec. 2.3): out = C + incoming,
-// tile by tile in the same issue order, driving the same tracker.
+// tile by tile in the same issue order, driving the same tracker and release.
 template <int BM, int BN>
 __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
   __shared__ uint32_t sh_word;
   Tile tl;
-  if (!decode_tile(p, tl)) return;
+  int slot = 0, agent = 0;
+  const int role = decode_block(p, tl, slot, agent);
+  if (role == kRoleNone) return;
+  if (role == kRoleRelease) {
+    release_chunk(p, slot, agent, &sh_word);
+    return;
+  }
   const int tid = threadIdx.x;
   const int m0 = tl.mi * BM;
   const int col_lo = tl.c * p.W;
@@ -317,14 +454,14 @@ __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
     f32x4 v = __builtin_nontemporal_load((const f32x4 *)(p.C + row * p.ldc + n0) + cc);
     if (!store_only)
       v += __builtin_nontemporal_load((const f32x4 *)(p.R + row * p.ldr + n0) + cc);
-    __builtin_nontemporal_store(v, (f32x4 *)(out_base + row * ld_out) + cc);
+    store_agent((f32x4 *)(out_base + row * ld_out) + cc, v);
   }
-  track_and_release(p, tl.c, &sh_word);
+  track_tile(p, tl.c);
 }
 
-// Clears tracker state: counters, flags, queue length and claims to 0, queue entries to empty.
+// Clears tracker state: counters, flags, queue length and error word to 0, queue entries to empty.
 __global__ void track_reset_kernel(uint32_t *track, int P) {
-  const int n = 4 * P + 1;
+  const int n = 3 * P + 2;
   for (int i = threadIdx.x; i < n; i += blockDim.x)
     track[i] = (i >= 2 * P && i < 3 * P) ? kEmpty : 0u;
 }

@@ -54,7 +54,7 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
     out["fwd"] = fwd.cpu().numpy()[:max(tp - 1, 0), :M, :W]
     tr = track.cpu().numpy().view(np.uint32)
     out.update(counter=tr[0:tp], ready=tr[tp:2 * tp], queue=tr[2 * tp:3 * tp],
-               queue_len=int(tr[3 * tp]), claim=tr[3 * tp + 1:4 * tp + 1])
+               queue_len=int(tr[3 * tp]), error=int(tr[3 * tp + 1]))
     return out
 
 

@@ -31,6 +31,7 @@ def _check_ints(got, want, tp, own):
     assert set(got["queue"][:n].tolist()) == set(want["queue"][:n].tolist())
     assert len(set(got["queue"][:n].tolist())) == n and own not in got["queue"][:n]
     assert np.all(got["queue"][n:] == 0xFFFFFFFF)
+    assert got["error"] == 0
 
 
 def _flags(step0, direct):
