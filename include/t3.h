@@ -81,7 +81,7 @@ typedef struct {
  * nj = q / Mt.  Workgroups are launched in issue order up to a permutation inside a
  * stage that groups tiles sharing operands on one XCD.
  *
- * Supported (tile_m, tile_n): (256,128), (128,256), (128,128).
+ * Supported (tile_m, tile_n): (256,256), (256,128), (128,256), (128,128).
  *
  * Tracker state (Sec. 4.2): one caller-owned device array of t3_track_words(tp)
  * uint32 words, cleared by t3_track_reset():

@@ -15,7 +15,7 @@ struct TileShape {
   int32_t m, n;
 };
 // preference order of t3_default_tile
-constexpr TileShape kTileShapes[] = {{256, 128}, {128, 256}, {128, 128}};
+constexpr TileShape kTileShapes[] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};
 constexpr int kNumTileShapes = sizeof(kTileShapes) / sizeof(kTileShapes[0]);
 constexpr int kNumXcd = 8;
 
@@ -36,11 +36,11 @@ bool tile_supported(int32_t tm, int32_t tn) {
 }
 
 void default_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
-  // the largest tile that still gives every compute unit two workgroups, else the smallest
+  // the largest tile that still gives every compute unit a workgroup, else the smallest
   const int64_t W = p->N / p->tp;
   for (int i = 0; i < kNumTileShapes; ++i) {
     const int64_t T = ceil_div(p->M, kTileShapes[i].m) * ceil_div(W, kTileShapes[i].n) * p->tp;
-    if (T >= 512) {
+    if (T >= 256) {
       *tm = kTileShapes[i].m;
       *tn = kTileShapes[i].n;
       return;
@@ -152,7 +152,8 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // the grid `lag` stages after the chunk's own tiles, far enough that those tiles have been
   // dispatched and are mostly finished when the release workgroups start.
   q.agents = (fused_like && !direct && p->tp > 1) ? T3_AGENTS : 0;
-  q.lag = (int32_t)(ceil_div(512, tpc > 0 ? tpc : 1) + 1);
+  const int64_t resident = (*tm == 256 && *tn == 256) ? 256 : 512;   // tile workgroups the chip holds
+  q.lag = (int32_t)(ceil_div(resident, tpc > 0 ? tpc : 1) + 1);
   if (q.lag > p->tp) q.lag = p->tp;
   q.rows_per_agent = q.agents ? (int32_t)ceil_div(p->M, q.agents) : 0;
   if ((T + (int64_t)q.agents * (p->tp - 1)) >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
@@ -174,13 +175,15 @@ inline unsigned grid_size(const t3k::Plan &q) {
 
 template <int MODE>
 void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
-  const dim3 grid(grid_size(q)), block(t3k::kThreads);
-  if (tm == 256 && tn == 128)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, MODE>), grid, block, 0, s, q);
+  const dim3 grid(grid_size(q));
+  if (tm == 256 && tn == 256)   // 8 wavefronts of 128 x 64, one workgroup per compute unit
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, 2, 4, 4, MODE>), grid, dim3(512), 0, s, q);
+  else if (tm == 256 && tn == 128)
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
   else if (tm == 128 && tn == 256)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, MODE>), grid, block, 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
   else
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, MODE>), grid, block, 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
 }
 
 }  // namespace
@@ -294,7 +297,9 @@ t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd
   if (empty) return T3_OK;
   const dim3 grid(grid_size(q)), block(t3k::kThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (tm == 256 && tn == 128)
+  if (tm == 256 && tn == 256)
+    hipLaunchKernelGGL((t3k::reduce_tile_kernel<256, 256>), grid, block, 0, s, q);
+  else if (tm == 256 && tn == 128)
     hipLaunchKernelGGL((t3k::reduce_tile_kernel<256, 128>), grid, block, 0, s, q);
   else if (tm == 128 && tn == 256)
     hipLaunchKernelGGL((t3k::reduce_tile_kernel<128, 256>), grid, block, 0, s, q);

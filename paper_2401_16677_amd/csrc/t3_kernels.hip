@@ -185,7 +185,7 @@ __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int W4 = p.W >> 2;
   const int r_end = min(p.M, (agent + 1) * p.rows_per_agent);
-  for (int r = agent * p.rows_per_agent + wave; r < r_end; r += kThreads / 64) {
+  for (int r = agent * p.rows_per_agent + wave; r < r_end; r += (int)(blockDim.x >> 6)) {
     const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
     f32x4 *dst = (f32x4 *)(p.fwd + ((int64_t)slot * p.M + r) * p.W);
     for (int c0 = lane; c0 < W4; c0 += 4 * 64) {
@@ -209,17 +209,22 @@ __device__ inline int swz(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 // sched_group_barrier masks
 constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
 
-template <int BM, int BN, int MODE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
+// WAVES_M x WAVES_N wavefronts per workgroup, each producing a (BM/WAVES_M) x (BN/WAVES_N)
+// block of the tile; NSTAGE LDS stages, NSTAGE-1 slabs in flight.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2)))
 void gemm_tile_kernel(const Plan p) {
-  constexpr int WM = BM / 2, WN = BN / 2;       // wavefront tile
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wavefront tile
   constexpr int FM = WM / 32, FN = WN / 32;     // 32x32 MFMA blocks per wavefront
-  constexpr int NA = BM / 64, NB = BN / 64;     // global->LDS copies per wavefront per slab
+  constexpr int NA = BM / 16 / NW, NB = BN / 16 / NW;   // global->LDS copies per wavefront per slab
   constexpr int NL = NA + NB;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int kBOff = BM * kRowBytes;
+  static_assert(NA * 16 * NW == BM && NB * 16 * NW == BN, "copies must tile the slab");
+  static_assert((NSTAGE - 2) * NL < 64, "vmcnt range");
 
-  __shared__ __attribute__((aligned(1024))) char lds[kStages * kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes];
   __shared__ uint32_t sh_word;
 
   Tile tl;
@@ -234,7 +239,7 @@ void gemm_tile_kernel(const Plan p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   const int m0 = tl.mi * BM;
   const int col_lo = tl.c * p.W;                 // chunk bounds in N
@@ -248,12 +253,12 @@ void gemm_tile_kernel(const Plan p) {
   uint32_t offA[NA], offB[NB];                   // byte offsets, rows clamped into range
 #pragma unroll
   for (int q = 0; q < NA; ++q)
-    offA[q] = (uint32_t)((min(m0 + wave * (BM / 4) + q * 16 + cp_row, p.M - 1) * p.lda + cp_chunk * 8) * 2);
+    offA[q] = (uint32_t)((min(m0 + wave * (BM / NW) + q * 16 + cp_row, p.M - 1) * p.lda + cp_chunk * 8) * 2);
 #pragma unroll
   for (int q = 0; q < NB; ++q)
-    offB[q] = (uint32_t)((min(n0 + wave * (BN / 4) + q * 16 + cp_row, col_hi - 1) * p.ldb + cp_chunk * 8) * 2);
-  const int ldsA_w = wave * (BM / 4) * kRowBytes;            // this wavefront's rows, stage 0
-  const int ldsB_w = kBOff + wave * (BN / 4) * kRowBytes;
+    offB[q] = (uint32_t)((min(n0 + wave * (BN / NW) + q * 16 + cp_row, col_hi - 1) * p.ldb + cp_chunk * 8) * 2);
+  const int ldsA_w = wave * (BM / NW) * kRowBytes;            // this wavefront's rows, stage 0
+  const int ldsB_w = kBOff + wave * (BN / NW) * kRowBytes;
 
   // The copies are issued as inline assembly: the compiler would otherwise wait for every
   // outstanding global->LDS copy (vmcnt(0)) before any LDS read, which defeats the prefetch.
@@ -288,8 +293,8 @@ void gemm_tile_kernel(const Plan p) {
   const int nkf = p.K / kBK;                     // full slabs
   const int ktail = p.K - nkf * kBK;             // 0, 8, 16 or 24 leftover elements of K
 
-  // Two slabs are always in flight.  Past the last slab the copies are repeated into stages
-  // nobody reads any more, so every wait below is for the same number of younger copies.
+  // NSTAGE-1 slabs are always in flight.  Past the last slab the copies are repeated into
+  // stages nobody reads any more, so every wait below is for the same number of younger copies.
   if (nkf > 0) issue_slab(0, 0);
 
   // ---- accumulators start from the incoming partial (fused) or zero.
@@ -319,7 +324,10 @@ void gemm_tile_kernel(const Plan p) {
         acc[i][j][e] = v;
       }
 
-  if (nkf > 0) issue_slab(min(1, nkf - 1), 1);
+  if (nkf > 0) {
+#pragma unroll
+    for (int st = 1; st < NSTAGE - 1; ++st) issue_slab(min(st, nkf - 1), st);
+  }
 
   bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
 #define T3_READ_FRAGS(fa, fb, fragA, fragB, stage_off)                                   \
@@ -336,12 +344,14 @@ void gemm_tile_kernel(const Plan p) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0); \
   }
 
-  // ---- main loop: slab kt is multiplied while slabs kt+1 and kt+2 are in flight.  The second
-  // half of a slab's products is issued after the next barrier, under the next slab's LDS reads.
+  // ---- main loop: slab kt is multiplied while the next NSTAGE-1 slabs are in flight.  The
+  // second half of a slab's products is issued after the next barrier, under the next slab's
+  // LDS reads.
+  constexpr int kWaitSlab = wait_vm((NSTAGE - 2) * NL);
   if (nkf > 0) {
-    __builtin_amdgcn_s_waitcnt(wait_vm(NL));       // slab 0 (and the incoming partial) landed
+    __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the incoming partial) landed
     __builtin_amdgcn_s_barrier();
-    issue_slab(min(2, nkf - 1), 2);
+    issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
     T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, 0);
     T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, 0);
     T3_MFMA_STEP(fa0, fb0);
@@ -349,9 +359,9 @@ void gemm_tile_kernel(const Plan p) {
     for (int kt = 1; kt < nkf; ++kt) {
       const int so = stage * kStageBytes;
       asm volatile("" ::: "memory");               // LDS reads above stay above the barrier
-      __builtin_amdgcn_s_waitcnt(wait_vm(NL) & kWaitLgkm0);   // own copies of slab kt landed, own LDS reads done
+      __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);   // own copies of slab kt landed, own LDS reads done
       __builtin_amdgcn_s_barrier();                // everyone's; all are done with the stage refilled next
-      issue_slab(min(kt + 2, nkf - 1), stage >= 1 ? stage - 1 : 2);
+      issue_slab(min(kt + NSTAGE - 1, nkf - 1), stage >= 1 ? stage - 1 : NSTAGE - 1);
       T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, so);
       T3_MFMA_STEP(fa1, fb1);                      // second half of slab kt-1
       T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, so);
@@ -361,7 +371,7 @@ void gemm_tile_kernel(const Plan p) {
       __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
       __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FM + FN, 0);
       __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
-      stage = stage == 2 ? 0 : stage + 1;
+      stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     }
     T3_MFMA_STEP(fa1, fb1);
     __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies

@@ -43,8 +43,8 @@ class Workload:
 # The five configurations, smallest first.
 WORKLOADS = {
     "tiny_outproj": Workload("tiny_outproj", 256, 1024, 256, 4, 0, 128, 128, index=0),
-    "gpt3_outproj": Workload("gpt3_outproj", 4096, 12288, 1536, 8, 3, 256, 128, index=1),
-    "gpt3_fc2": Workload("gpt3_fc2", 4096, 12288, 6144, 8, 5, 256, 128, a_dist="halfnormal",
+    "gpt3_outproj": Workload("gpt3_outproj", 4096, 12288, 1536, 8, 3, 256, 256, index=1),
+    "gpt3_fc2": Workload("gpt3_fc2", 4096, 12288, 6144, 8, 5, 256, 256, a_dist="halfnormal",
                          index=2),
     "wide_fc2": Workload("wide_fc2", 2048, 20480, 10240, 8, 7, 128, 256, index=3),
     "hightp_outproj": Workload("hightp_outproj", 8192, 18432, 1152, 16, 9, 256, 128, index=4),

@@ -47,6 +47,8 @@ EXACT_CASES = [
     (260, 1200, 136, 3, 0, (128, 256)),
     (512, 512, 64, 1, 0, (128, 128)),
     (100, 64, 8, 8, 5, (128, 128)),
+    (600, 1280, 104, 2, 0, (256, 256)),
+    (512, 2048, 160, 4, 3, (256, 256)),
 ]
 
 
@@ -117,7 +119,7 @@ def test_tiny_outproj_config_float_parity(gpu, oracle):
         _check_ints(got, want, w.tp, own)
 
 
-@pytest.mark.parametrize("tile", [(256, 128), (128, 256), (128, 128)])
+@pytest.mark.parametrize("tile", [(256, 256), (256, 128), (128, 256), (128, 128)])
 def test_float_multi_tile_ragged(gpu, oracle, tile):
     M, N, K, tp, rank = 700, 2080, 328, 4, 3
     w = wl.make_shape("ragged", M, N, K, tp, rank, *tile)

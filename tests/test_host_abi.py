@@ -39,7 +39,7 @@ def test_chunk_order_matches_oracle(oracle, tp):
 
 
 @pytest.mark.parametrize("M,N,tp,rank,tm,tn", [
-    (256, 1024, 4, 0, 128, 128), (4096, 12288, 8, 3, 256, 128), (2048, 20480, 8, 7, 128, 256),
+    (256, 1024, 4, 0, 128, 128), (4096, 12288, 8, 3, 256, 256), (2048, 20480, 8, 7, 128, 256),
     (300, 1000, 2, 1, 128, 128), (8192, 18432, 16, 9, 256, 128)])
 def test_tile_map_matches_oracle(oracle, M, N, tp, rank, tm, tn):
     p = t3.problem(M, N, 64, tp, rank, tm, tn)
@@ -57,9 +57,9 @@ def test_default_tile_gives_supported_shapes():
     for (M, N, tp) in [(256, 1024, 4), (4096, 12288, 8), (2048, 20480, 8), (8192, 18432, 16),
                        (1, 8, 2)]:
         tm, tn = t3.t3_default_tile(t3.problem(M, N, 64, tp, 0))
-        assert (tm, tn) in [(256, 128), (128, 256), (128, 128)]
+        assert (tm, tn) in [(256, 256), (256, 128), (128, 256), (128, 128)]
     assert t3.t3_default_tile(t3.problem(256, 1024, 256, 4, 0)) == (128, 128)
-    assert t3.t3_default_tile(t3.problem(4096, 12288, 1536, 8, 3)) == (256, 128)
+    assert t3.t3_default_tile(t3.problem(4096, 12288, 1536, 8, 3)) == (256, 256)
 
 
 def test_track_words():
