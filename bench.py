@@ -57,10 +57,13 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gpt3_outproj")
-    ap.add_argument("--direct", action="store_true",
-                    help="forwarded sums go straight to the forward buffer (T3_FLAG_FWD_DIRECT)")
+    ap.add_argument("--release", choices=["direct", "copy"], default="direct",
+                    help="direct: forwarded sums go straight to the forward buffer "
+                         "(T3_FLAG_FWD_DIRECT); copy: sums are added in place and release "
+                         "workgroups copy each triggered chunk to its forward slot")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     args = ap.parse_args()
+    args.direct = args.release == "direct"
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this path is one rank's kernel, with no "
                  "collective between GPUs; run with --gpus 1")
