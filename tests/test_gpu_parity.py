@@ -169,3 +169,64 @@ def test_integer_state_repeats(gpu, oracle):
         got = gpu.run_gpu(a, b, inc, tp, rank, tile)
         assert np.array_equal(got["R"], want["R"]) and np.array_equal(got["fwd"], want["fwd"])
         _check_ints(got, want, tp, want["own"])
+
+
+# ---------------------------------------------------------------- full-size configurations
+# The launch configuration bench.py times, checked on sampled rows the oracle computes one by
+# one (all N columns of each sampled row: every chunk, every tile column; rows drawn from
+# every tile row plus the first and last row), and on properties that hold at any size.
+FULL = ["gpt3_outproj", "gpt3_fc2", "wide_fc2", "hightp_outproj"]
+
+
+@pytest.mark.parametrize("direct", [True, False])
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_sampled_rows(gpu, oracle, name, direct):
+    import torch
+    w = wl.WORKLOADS[name]
+    print(f"workload={name} direct={direct} tile={w.tile_m}x{w.tile_n}", flush=True)
+    a, b, inc = wl.make_inputs(w)
+    rng = np.random.default_rng(w.seed)
+    Mt = -(-w.M // w.tile_m)
+    rows = sorted({0, w.M - 1} | {int(mi * w.tile_m + rng.integers(0, min(w.tile_m, w.M - mi * w.tile_m)))
+                                  for mi in range(Mt)})
+    rows = np.array(rows, dtype=np.int32)
+    S = oracle.reduce_rows(oracle.gemm_rows(a, b, rows=rows), inc, w.tp, rows=rows)   # (nrows, N)
+
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    R = torch.from_numpy(inc).to(dev)
+    fwd = torch.full((w.tp - 1, w.M, w.W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(w.tp), dtype=torch.int32, device=dev)
+    p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n,
+                   flags=t3.T3_FLAG_FWD_DIRECT if direct else 0)
+    t3.t3_track_reset(w.tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+
+    order, own = oracle.chunk_order(w.tp, w.rank)
+    tpc = oracle.tiles_per_chunk(w.M, w.N, w.tp, w.tile_m, w.tile_n)
+    tr = track.cpu().numpy().view(np.uint32)
+    assert np.all(tr[:w.tp] == tpc) and np.all(tr[w.tp:2 * w.tp] == 1)
+    assert tr[3 * w.tp] == w.tp - 1 and tr[3 * w.tp + 1] == 0
+    assert sorted(tr[2 * w.tp:3 * w.tp - 1].tolist()) == sorted(c for c in range(w.tp) if c != own)
+
+    idx = torch.from_numpy(rows.astype(np.int64)).to(dev)
+    Rg = R.index_select(0, idx).cpu().numpy()
+    fg = fwd.index_select(1, idx).cpu().numpy()
+    W = w.W
+    errs = []
+    for s in range(w.tp):
+        c = int(order[s])
+        want = S[:, c * W:(c + 1) * W]
+        if c == own:
+            errs.append(gpu.rel_err(Rg[:, c * W:(c + 1) * W], want))
+        else:
+            errs.append(gpu.rel_err(fg[s], want))
+            if direct:      # R keeps the incoming data on forwarded chunks
+                assert np.array_equal(Rg[:, c * W:(c + 1) * W], inc[rows][:, c * W:(c + 1) * W])
+            else:           # the slot is a copy of what was reduced in place
+                assert np.array_equal(Rg[:, c * W:(c + 1) * W], fg[s])
+    print(f"max normwise error over chunks {max(errs):.3e}", flush=True)
+    assert max(errs) <= TOL and max(errs) <= EXPECT
+    # any-size properties: nothing but finite values, and no forward slot left untouched
+    assert bool(torch.isfinite(fwd).all()) and not bool((fwd == gpu.SENTINEL).all(dim=2).any())
