@@ -7,6 +7,12 @@
 
 #include "t3_kernels.hip"
 
+// K-slab depth and LDS stage count of the 256 x 256 tile (64 KiB per stage at depth 64)
+#ifndef T3_BK256
+#define T3_BK256 64
+#define T3_NSTAGE256 2
+#endif
+
 namespace {
 
 thread_local int32_t g_last_hip_error = 0;
@@ -177,13 +183,13 @@ template <int MODE>
 void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
   const dim3 grid(grid_size(q));
   if (tm == 256 && tn == 256)   // 8 wavefronts of 128 x 64, one workgroup per compute unit
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, 2, 4, 4, MODE>), grid, dim3(512), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, T3_BK256, 2, 4, T3_NSTAGE256, MODE>), grid, dim3(512), 0, s, q);
   else if (tm == 256 && tn == 128)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 32, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
   else if (tm == 128 && tn == 256)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 32, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
   else
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 32, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
 }
 
 }  // namespace

@@ -201,28 +201,37 @@ __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// LDS layout of one stage: BM rows of A then BN rows of B, 64 bytes (4 chunks of 16) per row.
-// Row r keeps chunk k at position k ^ swz(r), which makes both the 1-KiB linear writes of the
-// global->LDS copies and the MFMA operand reads (consecutive rows, one k) conflict free.
-__device__ inline int swz(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
+// LDS layout of one stage: BM rows of A then BN rows of B; a row holds the BK bf16 of one tile
+// row of the slab (64 or 128 bytes = 4 or 8 chunks of 16).  Row r keeps chunk k at position
+// k ^ swz(r), which makes both the 1-KiB linear writes of the global->LDS copies and the MFMA
+// operand reads (consecutive rows, one k) bank-conflict free.
+template <int CPR>   // chunks per row
+__device__ inline int swz(int r) {
+  return CPR == 4 ? (((r >> 1) & 3) ^ ((r >> 3) & 1)) : ((r & 7) ^ ((r >> 3) & 1));
+}
 
 // sched_group_barrier masks
-constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
+constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100;
 
 // WAVES_M x WAVES_N wavefronts per workgroup, each producing a (BM/WAVES_M) x (BN/WAVES_N)
-// block of the tile; NSTAGE LDS stages, NSTAGE-1 slabs in flight.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
+// block of the tile; K-slabs of BK elements; NSTAGE LDS stages, NSTAGE-1 slabs in flight.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2)))
 void gemm_tile_kernel(const Plan p) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wavefront tile
   constexpr int FM = WM / 32, FN = WN / 32;     // 32x32 MFMA blocks per wavefront
-  constexpr int NA = BM / 16 / NW, NB = BN / 16 / NW;   // global->LDS copies per wavefront per slab
+  constexpr int kRowBytes = BK * 2;             // one LDS row
+  constexpr int CPR = BK / 8;                   // 16-byte chunks per row
+  constexpr int RPC = 64 / CPR;                 // rows filled by one 1-KiB copy
+  constexpr int KSTEPS = BK / 16;               // MFMA k-steps per slab
+  constexpr int NA = BM / RPC / NW, NB = BN / RPC / NW;   // copies per wavefront per slab
   constexpr int NL = NA + NB;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int kBOff = BM * kRowBytes;
-  static_assert(NA * 16 * NW == BM && NB * 16 * NW == BN, "copies must tile the slab");
-  static_assert((NSTAGE - 2) * NL < 64, "vmcnt range");
+  static_assert(NA * RPC * NW == BM && NB * RPC * NW == BN, "copies must tile the slab");
+  static_assert(NSTAGE >= 2 && (NSTAGE - 2) * NL < 64, "vmcnt range");
+  static_assert(KSTEPS % 2 == 0, "operand registers alternate between two sets");
 
   __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes];
   __shared__ uint32_t sh_word;
@@ -246,17 +255,23 @@ void gemm_tile_kernel(const Plan p) {
   const int col_hi = col_lo + p.W;
   const int n0 = col_lo + tl.nj * BN;
 
-  // ---- global -> LDS copy addressing.  Copy q of this wavefront fills 16 LDS rows (1 KiB):
-  // lane l lands in row l/4, position l%4, so it must fetch chunk (l%4) ^ swz(row).
-  const int cp_row = lane >> 2;
-  const int cp_chunk = (lane & 3) ^ swz(cp_row);
+  // ---- global -> LDS copy addressing.  Copy q of this wavefront fills RPC LDS rows (1 KiB):
+  // lane l lands in row l / CPR, position l % CPR, so it must fetch chunk (l % CPR) ^ swz(row).
+  const int cp_row = lane / CPR;
   uint32_t offA[NA], offB[NB];                   // byte offsets, rows clamped into range
+  int chunkA[NA], chunkB[NB];                    // the k-chunk each copy fetches
 #pragma unroll
-  for (int q = 0; q < NA; ++q)
-    offA[q] = (uint32_t)((min(m0 + wave * (BM / NW) + q * 16 + cp_row, p.M - 1) * p.lda + cp_chunk * 8) * 2);
+  for (int q = 0; q < NA; ++q) {
+    const int r = wave * (BM / NW) + q * RPC + cp_row;
+    chunkA[q] = (lane % CPR) ^ swz<CPR>(r);
+    offA[q] = (uint32_t)((min(m0 + r, p.M - 1) * p.lda + chunkA[q] * 8) * 2);
+  }
 #pragma unroll
-  for (int q = 0; q < NB; ++q)
-    offB[q] = (uint32_t)((min(n0 + wave * (BN / NW) + q * 16 + cp_row, col_hi - 1) * p.ldb + cp_chunk * 8) * 2);
+  for (int q = 0; q < NB; ++q) {
+    const int r = wave * (BN / NW) + q * RPC + cp_row;
+    chunkB[q] = (lane % CPR) ^ swz<CPR>(r);
+    offB[q] = (uint32_t)((min(n0 + r, col_hi - 1) * p.ldb + chunkB[q] * 8) * 2);
+  }
   const int ldsA_w = wave * (BM / NW) * kRowBytes;            // this wavefront's rows, stage 0
   const int ldsB_w = kBOff + wave * (BN / NW) * kRowBytes;
 
@@ -265,8 +280,8 @@ void gemm_tile_kernel(const Plan p) {
   // Waits for them are therefore explicit (s_waitcnt below).
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
   auto issue_slab = [&](int kt, int stage) {
-    const char *a = (const char *)p.A + (int64_t)kt * (kBK * 2);
-    const char *b = (const char *)p.B + (int64_t)kt * (kBK * 2);
+    const char *a = (const char *)p.A + (int64_t)kt * (BK * 2);
+    const char *b = (const char *)p.B + (int64_t)kt * (BK * 2);
     const uint32_t dst = lds_base + stage * kStageBytes;
 #pragma unroll
     for (int q = 0; q < NA; ++q)
@@ -283,15 +298,18 @@ void gemm_tile_kernel(const Plan p) {
   };
 
   // ---- MFMA operand addressing: lane reads row (lane & 31) of a 32-row block, k-chunk
-  // 2*kk + (lane >> 5).
-  const int fr = lane & 31, fh = lane >> 5, fs = swz(fr);
-  const int pos0 = ((0 + fh) ^ fs) * 16, pos1 = ((2 + fh) ^ fs) * 16;
-  const int fragA0 = (wm * WM + fr) * kRowBytes + pos0, fragA1 = (wm * WM + fr) * kRowBytes + pos1;
-  const int fragB0 = kBOff + (wn * WN + fr) * kRowBytes + pos0;
-  const int fragB1 = kBOff + (wn * WN + fr) * kRowBytes + pos1;
+  // 2*kk + (lane >> 5) of k-step kk.
+  const int fr = lane & 31, fh = lane >> 5, fs = swz<CPR>(fr);
+  int fragA[KSTEPS], fragB[KSTEPS];
+#pragma unroll
+  for (int kk = 0; kk < KSTEPS; ++kk) {
+    const int pos = ((2 * kk + fh) ^ fs) * 16;
+    fragA[kk] = (wm * WM + fr) * kRowBytes + pos;
+    fragB[kk] = kBOff + (wn * WN + fr) * kRowBytes + pos;
+  }
 
-  const int nkf = p.K / kBK;                     // full slabs
-  const int ktail = p.K - nkf * kBK;             // 0, 8, 16 or 24 leftover elements of K
+  const int nkf = p.K / BK;                      // full slabs
+  const int ktail = p.K - nkf * BK;              // leftover elements of K (a multiple of 8)
 
   // NSTAGE-1 slabs are always in flight.  Past the last slab the copies are repeated into
   // stages nobody reads any more, so every wait below is for the same number of younger copies.
@@ -329,32 +347,39 @@ void gemm_tile_kernel(const Plan p) {
     for (int st = 1; st < NSTAGE - 1; ++st) issue_slab(min(st, nkf - 1), st);
   }
 
-  bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
-#define T3_READ_FRAGS(fa, fb, fragA, fragB, stage_off)                                   \
-  {                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i)                                       \
-      fa[i] = *(const bf16x8 *)(lds + (stage_off) + fragA + i * 32 * kRowBytes);         \
-    _Pragma("unroll") for (int j = 0; j < FN; ++j)                                       \
-      fb[j] = *(const bf16x8 *)(lds + (stage_off) + fragB + j * 32 * kRowBytes);         \
-  }
-#define T3_MFMA_STEP(fa, fb)                                                             \
-  {                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i)                                       \
-      _Pragma("unroll") for (int j = 0; j < FN; ++j)                                     \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0); \
-  }
+  // Two sets of operand registers: k-step kk uses set kk & 1, and is read from LDS while the
+  // products of k-step kk-1 are issued.
+  bf16x8 fa[2][FM], fb[2][FN];
+  auto read_frags = [&](int kk, int stage_off) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+      fa[kk & 1][i] = *(const bf16x8 *)(lds + stage_off + fragA[kk] + i * 32 * kRowBytes);
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+      fb[kk & 1][j] = *(const bf16x8 *)(lds + stage_off + fragB[kk] + j * 32 * kRowBytes);
+  };
+  auto mfma_step = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+  };
 
   // ---- main loop: slab kt is multiplied while the next NSTAGE-1 slabs are in flight.  The
-  // second half of a slab's products is issued after the next barrier, under the next slab's
-  // LDS reads.
+  // products of a slab's last k-step are issued after the next barrier, under the next slab's
+  // first LDS reads.
   constexpr int kWaitSlab = wait_vm((NSTAGE - 2) * NL);
   if (nkf > 0) {
     __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the incoming partial) landed
     __builtin_amdgcn_s_barrier();
     issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
-    T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, 0);
-    T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, 0);
-    T3_MFMA_STEP(fa0, fb0);
+    read_frags(0, 0);
+#pragma unroll
+    for (int kk = 1; kk < KSTEPS; ++kk) {
+      read_frags(kk, 0);
+      mfma_step((kk - 1) & 1);
+    }
     int stage = 1;
     for (int kt = 1; kt < nkf; ++kt) {
       const int so = stage * kStageBytes;
@@ -362,18 +387,19 @@ void gemm_tile_kernel(const Plan p) {
       __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);   // own copies of slab kt landed, own LDS reads done
       __builtin_amdgcn_s_barrier();                // everyone's; all are done with the stage refilled next
       issue_slab(min(kt + NSTAGE - 1, nkf - 1), stage >= 1 ? stage - 1 : NSTAGE - 1);
-      T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, so);
-      T3_MFMA_STEP(fa1, fb1);                      // second half of slab kt-1
-      T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, so);
-      T3_MFMA_STEP(fa0, fb0);
-      __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, NL, 0);
-      __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FM + FN, 0);
-      __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
-      __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FM + FN, 0);
-      __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        read_frags(kk, so);
+        mfma_step((kk - 1) & 1);                   // kk == 0: last k-step of slab kt-1
+      }
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FM + FN, 0);
+        __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
+      }
       stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     }
-    T3_MFMA_STEP(fa1, fb1);
+    mfma_step((KSTEPS - 1) & 1);
     __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies
   }
   asm volatile("" ::: "memory");
@@ -381,31 +407,28 @@ void gemm_tile_kernel(const Plan p) {
   if (ktail) {
     // ragged end of K: through registers, chunks past K zeroed, into stage 0
     __syncthreads();
-    const int64_t kb = (int64_t)nkf * (kBK * 2);
-    const bool in = cp_chunk * 8 < ktail;
+    const int64_t kb = (int64_t)nkf * (BK * 2);
     const uint4 zero = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
       uint4 v = zero;
-      if (in) v = *(const uint4 *)((const char *)p.A + kb + offA[q]);
+      if (chunkA[q] * 8 < ktail) v = *(const uint4 *)((const char *)p.A + kb + offA[q]);
       *(uint4 *)(lds + ldsA_w + q * 1024 + lane * 16) = v;
     }
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       uint4 v = zero;
-      if (in) v = *(const uint4 *)((const char *)p.B + kb + offB[q]);
+      if (chunkB[q] * 8 < ktail) v = *(const uint4 *)((const char *)p.B + kb + offB[q]);
       *(uint4 *)(lds + ldsB_w + q * 1024 + lane * 16) = v;
     }
     __syncthreads();
-    T3_READ_FRAGS(fa0, fb0, fragA0, fragB0, 0);
-    T3_MFMA_STEP(fa0, fb0);
-    if (ktail > 16) {
-      T3_READ_FRAGS(fa1, fb1, fragA1, fragB1, 0);
-      T3_MFMA_STEP(fa1, fb1);
-    }
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk)
+      if (kk * 16 < ktail) {
+        read_frags(kk, 0);
+        mfma_step(kk & 1);
+      }
   }
-#undef T3_READ_FRAGS
-#undef T3_MFMA_STEP
 
   // ---- epilogue: one agent-scope store per accumulator register
   float *out_base;        // origin of this wavefront's tile in the output
