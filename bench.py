@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the fused sliced-GEMM + reduce-scatter-reduction path on one MI355X.
 
-One step = one pass of the whole hot path over one batch of synthetic input: tracker reset,
-then t3_gemm_rs_fused (tile issue in ring order, MFMA main loop, reduction epilogue,
+One step = one pass of the whole hot path over one batch of synthetic input: one call of
+t3_gemm_rs_fused (tile issue in ring order, MFMA main loop, reduction epilogue,
 track & trigger, release into the forward buffer).  Inputs are resident in HBM before the
 timed region.  Prints ONE JSON line: fused TFLOP/s (2*M*N*K / time), the roofline figure of
 the fused kernel measured with events on the launch stream, the unfused GEMM-then-reduce
@@ -62,6 +62,8 @@ def main():
                          "(T3_FLAG_FWD_DIRECT); copy: sums are added in place and release "
                          "workgroups copy each triggered chunk to its forward slot")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch the step's kernels one by one instead of replaying a HIP graph")
     args = ap.parse_args()
     args.direct = args.release == "direct"
     if args.gpus != 1:
@@ -87,14 +89,32 @@ def main():
     flags = t3.T3_FLAG_FWD_DIRECT if args.direct else 0
     p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n, flags=flags)
 
+    t3.t3_track_reset(w.tp, track)       # once: every launch leaves a clean bank for the next
+
     def fused_step():
-        t3.t3_track_reset(w.tp, track)
         t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
 
     def unfused_step():
-        t3.t3_track_reset(w.tp, track)
         t3.t3_gemm(p, A, B, C)
         t3.t3_rs_reduce(p, C, R, fwd, track)
+
+    def graphed(step):
+        """Capture one step (its kernels are launched on the capturing stream) and return a
+        function that replays it: one graph launch per step instead of one per kernel."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                      # warm the launch path outside capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step()
+        return g.replay
+
+    if not args.no_graph:
+        fused_step = graphed(fused_step)
+        unfused_step = graphed(unfused_step)
 
     def timed(step, n):
         torch.cuda.synchronize()
@@ -109,15 +129,15 @@ def main():
     for _ in range(args.warmup):
         fused_step()
     t_fused = timed(fused_step, args.steps)
-    tr = track.cpu().numpy()
-    assert int(tr[:w.tp].sum()) == w.tp * t3.t3_tiles_per_chunk(p), "tracker did not complete"
+    tr = t3.read_track(track, w.tp)
+    assert int(tr["counter"].sum()) == w.tp * t3.t3_tiles_per_chunk(p) and tr["error"] == 0, \
+        "tracker did not complete"
 
     # kernel-only duration of the fused kernel, events on the stream it is launched on
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(args.steps)]
     torch.cuda.synchronize()
     for e0, e1 in ev:
-        t3.t3_track_reset(w.tp, track)
         e0.record()
         t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
         e1.record()
@@ -153,7 +173,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "tp": w.tp, "rank": w.rank,
                    "tile": [w.tile_m, w.tile_n],
-                   "release": "direct" if args.direct else "copy"},
+                   "release": "direct" if args.direct else "copy",
+                   "launch": "eager" if args.no_graph else "hip_graph"},
         "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "unfused_ms_per_step": t_unfused * 1e3,
         "speedup_vs_unfused": t_unfused / t_fused,

@@ -83,19 +83,26 @@ typedef struct {
  *
  * Supported (tile_m, tile_n): (256,256), (256,128), (128,256), (128,128).
  *
- * Tracker state (Sec. 4.2): one caller-owned device array of t3_track_words(tp)
- * uint32 words, cleared by t3_track_reset():
+ * Tracker state (Sec. 4.2): one caller-owned device array of t3_track_words(tp) uint32
+ * words, cleared once by t3_track_reset().  It holds two banks of 3*tp + 2 words
  *   [0, tp)        counter[c]  tiles of chunk c that have landed
  *   [tp, 2tp)      ready[c]    1 once counter[c] == tpc
  *   [2tp, 3tp)     queue[i]    chunk ids in trigger order (forwarded chunks only, so at
  *                              most tp-1 entries are used); 0xFFFFFFFF = empty
  *   [3tp]          queue_len
- *   [3tp+1]        error       0, or 1 if a release workgroup gave up waiting for a chunk
+ *   [3tp+1]        done        workgroups of the launch that have finished
+ * followed by two global words
+ *   [6tp+4]        gen         launches completed since the reset
+ *   [6tp+5]        error       0, or 1 if a release workgroup gave up waiting for a chunk
  *                              (cannot happen in a launch that ran to completion)
- * Counter, ready and queue-as-a-set are deterministic; the order of queue entries
- * follows the order in which chunks actually completed on the device.  A tile's results are
- * visible to the whole device before it is counted, so a consumer that observes ready[c] (with
- * an acquiring load) may read chunk c.
+ * A launch of t3_gemm_rs_fused / t3_rs_reduce works in bank gen & 1; its last workgroup
+ * clears the other bank and increments gen.  So consecutive launches need no reset in
+ * between, and after a launch has completed its results are in bank (gen - 1) & 1.  A
+ * launch that executes no tile (empty problem, tile_limit == 0) leaves the state untouched.
+ * Counter, ready and queue-as-a-set are deterministic; the order of queue entries follows
+ * the order in which chunks actually completed on the device.  A tile's results are visible
+ * to the whole device before it is counted, so a consumer that observes ready[c] (with an
+ * acquiring load) may read chunk c.
  */
 
 /* Ring order of `rank` and the chunk it keeps.  Host pointers: order[tp], own[1]. */
@@ -115,7 +122,8 @@ t3_status t3_tile_of(const t3_problem *p, int64_t t, int32_t *s, int32_t *c, int
 /* Number of uint32 words of tracker state for a ring of size tp (0 if tp < 1). */
 int64_t t3_track_words(int32_t tp);
 
-/* Clears the tracker state (a small fill kernel on `stream`).  track: device. */
+/* Clears the tracker state (a small fill kernel on `stream`).  Needed once before the first
+   launch that uses `track`, not between launches.  track: device. */
 t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
 
 /*
@@ -134,7 +142,8 @@ t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
  *                           from R by release workgroups of the same launch, which wait on
  *                           the chunk's ready flag) and left untouched otherwise.  T3_FLAG_FWD_DIRECT: executed tiles
  *                           are written as they finish.  May be NULL if tp == 1.
- *   track                   tracker state, must have been reset on the same stream
+ *   track                   tracker state (reset once; launches sharing it must be ordered
+ *                           on one stream)
  * fp32 accumulation order is unspecified; integer outputs are exact.
  */
 t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, float *R,

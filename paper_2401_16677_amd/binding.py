@@ -170,7 +170,14 @@ def t3_rs_reduce(p, C, R, fwd, track, stream=None):
                               _stream(stream)), "t3_rs_reduce")
 
 
-def track_views(track, tp):
-    """Slices of a tracker-state tensor: counter, ready, queue, queue_len, error."""
-    return {"counter": track[0:tp], "ready": track[tp:2 * tp], "queue": track[2 * tp:3 * tp],
-            "queue_len": track[3 * tp:3 * tp + 1], "error": track[3 * tp + 1:3 * tp + 2]}
+def read_track(track, tp):
+    """Results of the launch that last completed, from a tracker-state tensor (synchronises):
+    counter, ready, queue (numpy uint32), queue_len, done, gen, error."""
+    import numpy as np
+    w = track.detach().cpu().numpy().view(np.uint32)
+    bank_words = 3 * tp + 2
+    gen, error = int(w[2 * bank_words]), int(w[2 * bank_words + 1])
+    b = w[((gen - 1) & 1) * bank_words:][:bank_words]
+    return {"counter": b[0:tp].copy(), "ready": b[tp:2 * tp].copy(),
+            "queue": b[2 * tp:3 * tp].copy(), "queue_len": int(b[3 * tp]),
+            "done": int(b[3 * tp + 1]), "gen": gen, "error": error}

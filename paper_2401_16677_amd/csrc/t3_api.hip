@@ -163,6 +163,10 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   if (q.lag > p->tp) q.lag = p->tp;
   q.rows_per_agent = q.agents ? (int32_t)ceil_div(p->M, q.agents) : 0;
   if ((T + (int64_t)q.agents * (p->tp - 1)) >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
+  // workgroups that will do work: the tiles below the limit and the release workgroups of the
+  // forwarded chunks those tiles complete
+  const int64_t done_chunks = tpc > 0 ? q.limit / tpc : 0;
+  q.expected_done = (int32_t)(q.limit + q.agents * (done_chunks < p->tp - 1 ? done_chunks : p->tp - 1));
   return T3_OK;
 }
 
@@ -256,7 +260,7 @@ t3_status t3_tile_of(const t3_problem *p, int64_t t, int32_t *s, int32_t *c, int
   return T3_OK;
 }
 
-int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 3ll * tp + 2; }
+int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 2 * (3ll * tp + 2) + 2; }
 
 t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream) {
   if (!track) return T3_ERR_NULL;

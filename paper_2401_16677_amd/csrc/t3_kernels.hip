@@ -63,6 +63,7 @@ struct Plan {
   int32_t Mt, Wt, tpc;
   int32_t xcd_nbm, xcd_bmk, xcd_bnk;   // XCD grouping of a stage's tiles; xcd_nbm == 0: none
   int32_t agents, lag, rows_per_agent; // release workgroups per chunk, their lag in stages
+  int32_t expected_done;               // workgroups of this launch that do work
   uint32_t flags;
 };
 
@@ -70,12 +71,48 @@ struct Tile {
   int s, c, mi, nj;
 };
 
-// Tracker state layout (uint32 words): counter[P] ready[P] queue[P] queue_len error.
-__device__ inline uint32_t *trk_counter(const Plan &p) { return p.track; }
-__device__ inline uint32_t *trk_ready(const Plan &p) { return p.track + p.P; }
-__device__ inline uint32_t *trk_queue(const Plan &p) { return p.track + 2 * p.P; }
-__device__ inline uint32_t *trk_queue_len(const Plan &p) { return p.track + 3 * p.P; }
-__device__ inline uint32_t *trk_error(const Plan &p) { return p.track + 3 * p.P + 1; }
+// Tracker state (uint32 words): two banks of { counter[P] ready[P] queue[P] queue_len done },
+// then the globals { gen, error }.  A launch works in bank gen & 1; the last workgroup of the
+// launch to finish clears the other bank and increments gen, so the next launch starts from a
+// clean bank without a reset kernel in between, and the caller finds the results of the launch
+// that just ended in bank (gen - 1) & 1.
+__device__ inline int trk_bank_words(int P) { return 3 * P + 2; }
+struct Trk {
+  uint32_t *counter, *ready, *queue, *queue_len, *done;   // this launch's bank
+  uint32_t *other;                                         // the bank to clear at the end
+  uint32_t *gen, *error;
+};
+__device__ inline Trk trk_open(const Plan &p) {
+  Trk t;
+  t.gen = p.track + 2 * trk_bank_words(p.P);
+  t.error = t.gen + 1;
+  const uint32_t g = __hip_atomic_load(t.gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  uint32_t *b = p.track + (g & 1u) * trk_bank_words(p.P);
+  t.counter = b;
+  t.ready = b + p.P;
+  t.queue = b + 2 * p.P;
+  t.queue_len = b + 3 * p.P;
+  t.done = b + 3 * p.P + 1;
+  t.other = p.track + ((g & 1u) ^ 1u) * trk_bank_words(p.P);
+  return t;
+}
+__device__ inline void trk_clear_bank(uint32_t *b, int P) {
+  for (int i = 0; i < 3 * P + 2; ++i)
+    __hip_atomic_store(&b[i], (i >= 2 * P && i < 3 * P) ? kEmpty : 0u, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by thread 0 of every workgroup that did work, as its last act; d = the value its
+// increment of `done` returned.
+__device__ inline void trk_close_if_last(const Plan &p, const Trk &t, uint32_t d) {
+  if (d + 1u == (uint32_t)p.expected_done) {
+    trk_clear_bank(t.other, p.P);
+    __hip_atomic_fetch_add(t.gen, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+__device__ inline void trk_workgroup_done(const Plan &p, const Trk &t) {
+  trk_close_if_last(
+      p, t, __hip_atomic_fetch_add(t.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
 
 // Index j of a tile inside its stage -> tile.  Workgroups are dealt round-robin to the 8 XCDs,
 // so workgroup j of a stage lands on XCD j % 8; that XCD gets a compact block of
@@ -143,21 +180,23 @@ __device__ inline void store_agent(f32x4 *p, f32x4 v) {
 // acknowledged (vmcnt == 0 in every wavefront, then the barrier) the tile is counted.  A
 // device-scope release fence instead would write back the whole L2 for every tile and costs
 // several times the reduction itself.
-__device__ inline void track_tile(const Plan &p, int c) {
+__device__ inline void track_tile(const Plan &p, const Trk &t, int c) {
   __builtin_amdgcn_s_waitcnt(kWaitAll);
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t old = __hip_atomic_fetch_add(&trk_counter(p)[c], 1u, __ATOMIC_RELAXED,
+    // both increments are in flight together: one round trip at the end of a tile, not two
+    const uint32_t old = __hip_atomic_fetch_add(&t.counter[c], 1u, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t d = __hip_atomic_fetch_add(t.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1u == (uint32_t)p.tpc) {   // the landing that reaches the threshold triggers
       if (c != p.own) {
-        const uint32_t pos = __hip_atomic_fetch_add(trk_queue_len(p), 1u, __ATOMIC_RELAXED,
+        const uint32_t pos = __hip_atomic_fetch_add(t.queue_len, 1u, __ATOMIC_RELAXED,
                                                     __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&trk_queue(p)[pos], (uint32_t)c, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&t.queue[pos], (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      __hip_atomic_store(&trk_ready(p)[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&t.ready[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    trk_close_if_last(p, t, d);
   }
 }
 
@@ -167,19 +206,23 @@ __device__ inline void track_tile(const Plan &p, int c) {
 // not (a broken launch), the workgroup gives up after kSpinLimit polls and raises the error word.
 __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_t *sh) {
   if ((int64_t)(slot + 1) * p.tpc > p.limit) return;   // this chunk will not complete
+  const Trk t = trk_open(p);
   int c = p.rank + slot;
   if (c >= p.P) c -= p.P;
   if (threadIdx.x == 0) {
     int spins = 0;
-    while (__hip_atomic_load(&trk_ready(p)[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
+    while (__hip_atomic_load(&t.ready[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
            ++spins < kSpinLimit)
       __builtin_amdgcn_s_sleep(16);
     const uint32_t ok = spins < kSpinLimit;
-    if (!ok) __hip_atomic_fetch_or(trk_error(p), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!ok) __hip_atomic_fetch_or(t.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *sh = ok;
   }
   __syncthreads();
-  if (!*sh) return;
+  if (!*sh) {            // gave up: still count as finished so that the launch closes its bank
+    if (threadIdx.x == 0) trk_workgroup_done(p, t);
+    return;
+  }
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of R
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -198,6 +241,9 @@ __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_
         if (c0 + u * 64 < W4) __builtin_nontemporal_store(v[u], dst + c0 + u * 64);
     }
   }
+  __builtin_amdgcn_s_waitcnt(kWaitAll);
+  __syncthreads();
+  if (threadIdx.x == 0) trk_workgroup_done(p, t);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -244,6 +290,9 @@ void gemm_tile_kernel(const Plan p) {
     if (MODE == kModeFused) release_chunk(p, slot, agent, &sh_word);
     return;
   }
+
+  Trk trk;
+  if (MODE == kModeFused) trk = trk_open(p);   // reads gen now; used when the tile is done
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -453,7 +502,7 @@ void gemm_tile_kernel(const Plan p) {
           store_agent((float *)(sb + out_voff), acc[i][j][e]);
       }
 
-  if (MODE == kModeFused) track_tile(p, tl.c);
+  if (MODE == kModeFused) track_tile(p, trk, tl.c);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -470,6 +519,7 @@ __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
     release_chunk(p, slot, agent, &sh_word);
     return;
   }
+  const Trk trk = trk_open(p);
   const int tid = threadIdx.x;
   const int m0 = tl.mi * BM;
   const int col_lo = tl.c * p.W;
@@ -489,14 +539,16 @@ __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
       v += __builtin_nontemporal_load((const f32x4 *)(p.R + row * p.ldr + n0) + cc);
     store_agent((f32x4 *)(out_base + row * ld_out) + cc, v);
   }
-  track_tile(p, tl.c);
+  track_tile(p, trk, tl.c);
 }
 
-// Clears tracker state: counters, flags, queue length and error word to 0, queue entries to empty.
+// Clears tracker state: both banks (queue entries to empty, the rest to 0), gen and error to 0.
 __global__ void track_reset_kernel(uint32_t *track, int P) {
-  const int n = 3 * P + 2;
-  for (int i = threadIdx.x; i < n; i += blockDim.x)
-    track[i] = (i >= 2 * P && i < 3 * P) ? kEmpty : 0u;
+  const int bank = 3 * P + 2, n = 2 * bank + 2;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    const int j = i < 2 * bank ? i % bank : -1;
+    track[i] = (j >= 2 * P && j < 3 * P) ? kEmpty : 0u;
+  }
 }
 
 }  // namespace t3k

@@ -52,9 +52,9 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
     out["R"] = Rh[:M, :N]
     out["R_pad"] = Rh[:M, N:]
     out["fwd"] = fwd.cpu().numpy()[:max(tp - 1, 0), :M, :W]
-    tr = track.cpu().numpy().view(np.uint32)
-    out.update(counter=tr[0:tp], ready=tr[tp:2 * tp], queue=tr[2 * tp:3 * tp],
-               queue_len=int(tr[3 * tp]), error=int(tr[3 * tp + 1]))
+    tr = t3.read_track(track, tp)
+    out.update(counter=tr["counter"], ready=tr["ready"], queue=tr["queue"],
+               queue_len=tr["queue_len"], error=tr["error"], gen=tr["gen"])
     return out
 
 

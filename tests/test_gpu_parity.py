@@ -157,8 +157,9 @@ def test_default_tile_and_k_zero_and_empty(gpu, oracle):
     t3.t3_track_reset(tp, track)
     t3.t3_gemm_rs_fused(p0, A, B, R, fwd, track)
     torch.cuda.synchronize()
-    tr = track.cpu().numpy()
-    assert np.all(tr[:2 * tp] == 0) and tr[3 * tp] == 0
+    tr = t3.read_track(track, tp)
+    assert np.all(tr["counter"] == 0) and np.all(tr["ready"] == 0) and tr["queue_len"] == 0
+    assert tr["gen"] == 0
 
 
 def test_integer_state_repeats(gpu, oracle):
@@ -205,10 +206,10 @@ def test_full_size_sampled_rows(gpu, oracle, name, direct):
 
     order, own = oracle.chunk_order(w.tp, w.rank)
     tpc = oracle.tiles_per_chunk(w.M, w.N, w.tp, w.tile_m, w.tile_n)
-    tr = track.cpu().numpy().view(np.uint32)
-    assert np.all(tr[:w.tp] == tpc) and np.all(tr[w.tp:2 * w.tp] == 1)
-    assert tr[3 * w.tp] == w.tp - 1 and tr[3 * w.tp + 1] == 0
-    assert sorted(tr[2 * w.tp:3 * w.tp - 1].tolist()) == sorted(c for c in range(w.tp) if c != own)
+    tr = t3.read_track(track, w.tp)
+    assert np.all(tr["counter"] == tpc) and np.all(tr["ready"] == 1)
+    assert tr["queue_len"] == w.tp - 1 and tr["error"] == 0 and tr["gen"] == 1
+    assert sorted(tr["queue"][:w.tp - 1].tolist()) == sorted(c for c in range(w.tp) if c != own)
 
     idx = torch.from_numpy(rows.astype(np.int64)).to(dev)
     Rg = R.index_select(0, idx).cpu().numpy()
@@ -230,3 +231,84 @@ def test_full_size_sampled_rows(gpu, oracle, name, direct):
     assert max(errs) <= TOL and max(errs) <= EXPECT
     # any-size properties: nothing but finite values, and no forward slot left untouched
     assert bool(torch.isfinite(fwd).all()) and not bool((fwd == gpu.SENTINEL).all(dim=2).any())
+
+
+def test_graph_replays_match_eager(gpu, oracle):
+    """The step bench.py times (tracker reset + fused call) captured in a HIP graph: every
+    replay, with eager work and synchronisation in between, must reproduce the eager result."""
+    import torch
+    M, N, K, tp, rank, tile = 512, 2048, 192, 4, 1, (256, 256)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=77)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True,
+                             fwd_init=np.zeros((tp - 1, M, N // tp), np.float32))
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    inc_dev = torch.from_numpy(inc).to(dev)
+    R = inc_dev.clone()
+    fwd = torch.zeros((tp - 1, M, N // tp), dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(tp), dtype=torch.int32, device=dev)
+    p = t3.problem(M, N, K, tp, rank, *tile, flags=t3.T3_FLAG_FWD_DIRECT)
+
+    def step():
+        t3.t3_track_reset(tp, track)
+        t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        step()
+    for rep in range(4):
+        R.copy_(inc_dev)                 # eager work between replays
+        fwd.zero_()
+        track.fill_(0x5A5A5A5A)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        own = want["own"]
+        W = N // tp
+        assert np.array_equal(fwd.cpu().numpy(), want["fwd"]), rep
+        assert np.array_equal(R.cpu().numpy()[:, own * W:(own + 1) * W], want["owned"]), rep
+        tr = t3.read_track(track, tp)
+        assert np.array_equal(tr["counter"], want["counter"]) and tr["queue_len"] == tp - 1, rep
+        assert tr["gen"] == 1, rep
+
+
+def test_consecutive_launches_need_no_reset(gpu, oracle):
+    """One reset, then several launches on the same tracker state: each finds a clean bank and
+    leaves its own results behind; gen counts the launches (also partial ones)."""
+    import torch
+    M, N, K, tp, rank, tile = 384, 1536, 64, 3, 2, (128, 128)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=91)
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    inc_dev = torch.from_numpy(inc).to(dev)
+    R = inc_dev.clone()
+    W = N // tp
+    fwd = torch.zeros((tp - 1, M, W), dtype=torch.float32, device=dev)
+    track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+    t3.t3_track_reset(tp, track)
+    tpc = oracle.tiles_per_chunk(M, N, tp, *tile)
+    launches = [(-1, 0), (tpc + 3, 0), (-1, t3.T3_FLAG_FWD_DIRECT), (-1, 0), (2 * tpc, 0)]
+    for n, (limit, flags) in enumerate(launches, start=1):
+        R.copy_(inc_dev)
+        fwd.fill_(gpu.SENTINEL)
+        p = t3.problem(M, N, K, tp, rank, *tile, tile_limit=limit, flags=flags)
+        t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+        torch.cuda.synchronize()
+        want = oracle.fused_path(a, b, inc, tp, rank, *tile, tile_limit=limit,
+                                 fwd_direct=bool(flags & t3.T3_FLAG_FWD_DIRECT),
+                                 fwd_init=np.full((tp - 1, M, W), gpu.SENTINEL, np.float32))
+        tr = t3.read_track(track, tp)
+        print(f"launch {n}: limit={limit} flags={flags} gen={tr['gen']}", flush=True)
+        assert tr["gen"] == n and tr["error"] == 0
+        assert np.array_equal(tr["counter"], want["counter"])
+        assert np.array_equal(tr["ready"], want["ready"])
+        assert tr["queue_len"] == want["queue_len"]
+        assert set(tr["queue"][:tr["queue_len"]].tolist()) == set(want["queue"][:want["queue_len"]].tolist())
+        assert np.array_equal(R.cpu().numpy(), want["R"])
+        assert np.array_equal(fwd.cpu().numpy(), want["fwd"])
