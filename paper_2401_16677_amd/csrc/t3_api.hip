@@ -4,14 +4,10 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+#include <stdio.h>
 
 #include "t3_kernels.hip"
-
-// K-slab depth and LDS stage count of the 256 x 256 tile (64 KiB per stage at depth 64)
-#ifndef T3_BK256
-#define T3_BK256 64
-#define T3_NSTAGE256 2
-#endif
 
 namespace {
 
@@ -158,11 +154,21 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // the grid `lag` stages after the chunk's own tiles, far enough that those tiles have been
   // dispatched and are mostly finished when the release workgroups start.
   q.agents = (fused_like && !direct && p->tp > 1) ? T3_AGENTS : 0;
-  const int64_t resident = (*tm == 256 && *tn == 256) ? 256 : 512;   // tile workgroups the chip holds
+  const int64_t resident = (*tm == 128 && *tn == 128) ? 512 : 256;   // tile workgroups the chip holds
   q.lag = (int32_t)(ceil_div(resident, tpc > 0 ? tpc : 1) + 1);
   if (q.lag > p->tp) q.lag = p->tp;
   q.rows_per_agent = q.agents ? (int32_t)ceil_div(p->M, q.agents) : 0;
   if ((T + (int64_t)q.agents * (p->tp - 1)) >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
+  // start-up phase offsets (experiment knobs: T3_STAGGER="groups,window_ns")
+  q.stagger_blocks = q.stagger_groups = q.stagger_ticks = 0;
+  if (const char *e = getenv("T3_STAGGER")) {
+    int g = 0, ns = 0;
+    if (sscanf(e, "%d,%d", &g, &ns) == 2 && g > 1 && ns > 0) {
+      q.stagger_groups = g;
+      q.stagger_ticks = ns / 10 / g;          // 100 MHz ticks between consecutive groups
+      q.stagger_blocks = (int32_t)resident;
+    }
+  }
   // workgroups that will do work: the tiles below the limit and the release workgroups of the
   // forwarded chunks those tiles complete
   const int64_t done_chunks = tpc > 0 ? q.limit / tpc : 0;
@@ -186,14 +192,17 @@ inline unsigned grid_size(const t3k::Plan &q) {
 template <int MODE>
 void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
   const dim3 grid(grid_size(q));
-  if (tm == 256 && tn == 256)   // 8 wavefronts of 128 x 64, one workgroup per compute unit
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, T3_BK256, 2, 4, T3_NSTAGE256, MODE>), grid, dim3(512), 0, s, q);
+  // K-slabs of 64 everywhere.  256 x 256: 8 wavefronts of 128 x 64, two 64-KiB stages; the
+  // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
+  // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.
+  if (tm == 256 && tn == 256)
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE>), grid, dim3(512), 0, s, q);
   else if (tm == 256 && tn == 128)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 32, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE>), grid, dim3(512), 0, s, q);
   else if (tm == 128 && tn == 256)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 32, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE>), grid, dim3(512), 0, s, q);
   else
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 32, 2, 2, 3, MODE>), grid, dim3(256), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE>), grid, dim3(256), 0, s, q);
 }
 
 }  // namespace

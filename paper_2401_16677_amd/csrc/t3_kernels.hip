@@ -31,9 +31,6 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *global_void_ptr;
 
 constexpr int kThreads = 256;
-constexpr int kBK = 32;               // bf16 elements of K per slab
-constexpr int kRowBytes = 64;         // one LDS row = one tile row of a slab
-constexpr int kStages = 3;
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kSpinLimit = 1 << 22;   // polls of a release workgroup before it gives up
 
@@ -64,6 +61,7 @@ struct Plan {
   int32_t xcd_nbm, xcd_bmk, xcd_bnk;   // XCD grouping of a stage's tiles; xcd_nbm == 0: none
   int32_t agents, lag, rows_per_agent; // release workgroups per chunk, their lag in stages
   int32_t expected_done;               // workgroups of this launch that do work
+  int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
   uint32_t flags;
 };
 
@@ -164,6 +162,20 @@ __device__ inline int decode_block(const Plan &p, Tile &tl, int &slot, int &agen
   return slot <= p.P - 2 ? kRoleRelease : kRoleNone;
 }
 
+// Phase offsets at start-up.  All workgroups of the first wave of tiles start together and would
+// reach their reduction traffic (incoming tile in, sums out) together, an HBM-bound burst during
+// which no matrix core works.  The first `stagger_blocks` workgroups are put into
+// `stagger_groups` phase groups; group g starts g * stagger_ticks (100 MHz ticks) late.  Later
+// workgroups are dispatched as earlier ones retire, so the offsets persist through the launch.
+__device__ inline void stagger_start(const Plan &p) {
+  const int b = blockIdx.x;
+  if (b >= p.stagger_blocks) return;
+  const int grp = ((b >> 3) + (b >> 8)) % p.stagger_groups;
+  if (!grp) return;
+  const uint64_t t0 = wall_clock64(), wait = (uint64_t)grp * (uint64_t)p.stagger_ticks;
+  while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(8);
+}
+
 // Stores that are visible to every XCD once acknowledged: agent scope, i.e. the sc1 bit, which
 // writes through the issuing XCD's L2.  (Plain and non-temporal stores stay in that L2 until a
 // release fence writes the whole cache back.)
@@ -247,52 +259,62 @@ __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// LDS layout of one stage: BM rows of A then BN rows of B; a row holds the BK bf16 of one tile
-// row of the slab (64 or 128 bytes = 4 or 8 chunks of 16).  Row r keeps chunk k at position
-// k ^ swz(r), which makes both the 1-KiB linear writes of the global->LDS copies and the MFMA
-// operand reads (consecutive rows, one k) bank-conflict free.
-template <int CPR>   // chunks per row
-__device__ inline int swz(int r) {
-  return CPR == 4 ? (((r >> 1) & 3) ^ ((r >> 3) & 1)) : ((r & 7) ^ ((r >> 3) & 1));
-}
+// LDS layout of one stage: BM rows of A then BN rows of B; a row holds the 64 bf16 of one tile
+// row of the K-slab (128 bytes = 8 chunks of 16).  Row r keeps chunk k at position k ^ swz(r),
+// which makes both the 1-KiB linear writes of the global->LDS copies (8 rows each) and the MFMA
+// operand reads (16 consecutive rows, one chunk) bank-conflict free.
+__device__ inline int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+constexpr int kBK = 64;               // bf16 elements of K per slab
+constexpr int kRowBytes = kBK * 2;    // one LDS row
+constexpr int kCPR = 8;               // 16-byte chunks per row
+constexpr int kRPC = 8;               // rows filled by one 1-KiB copy
 
 // sched_group_barrier masks
 constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100;
 
 // WAVES_M x WAVES_N wavefronts per workgroup, each producing a (BM/WAVES_M) x (BN/WAVES_N)
-// block of the tile; K-slabs of BK elements; NSTAGE LDS stages, NSTAGE-1 slabs in flight.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
+// block of the tile out of 16 x 16 MFMA blocks; NSTAGE LDS stages, NSTAGE-1 slabs in flight.
+//
+// The products are formed transposed (the B rows go in as the MFMA's first operand, the A rows
+// as its second), so that a lane ends up holding, per block, one output row and FOUR
+// CONSECUTIVE COLUMNS: the incoming partial is read and the sum written with 16-byte accesses,
+// 32 of each per wavefront for a 128 x 64 wavefront tile, all in flight together.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2)))
 void gemm_tile_kernel(const Plan p) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wavefront tile
-  constexpr int FM = WM / 32, FN = WN / 32;     // 32x32 MFMA blocks per wavefront
-  constexpr int kRowBytes = BK * 2;             // one LDS row
-  constexpr int CPR = BK / 8;                   // 16-byte chunks per row
-  constexpr int RPC = 64 / CPR;                 // rows filled by one 1-KiB copy
-  constexpr int KSTEPS = BK / 16;               // MFMA k-steps per slab
-  constexpr int NA = BM / RPC / NW, NB = BN / RPC / NW;   // copies per wavefront per slab
+  constexpr int FM = WM / 16, FN = WN / 16;     // 16x16 MFMA blocks per wavefront
+  constexpr int MH = FM > 4 ? 2 : 1;            // a k-step is taken in MH passes over the rows,
+  constexpr int FMH = FM / MH;                  //   FMH row blocks each, to bound operand registers
+  constexpr int KS = kBK / 32;                  // MFMA k-steps per slab
+  constexpr int US = KS * MH;                   // micro-steps (row pass of a k-step) per slab
+  constexpr int NA = BM / kRPC / NW, NB = BN / kRPC / NW;   // copies per wavefront per slab
   constexpr int NL = NA + NB;
+  constexpr int SPREAD = US >= 4 ? 2 : 1;       // micro-steps over which a slab's copies are issued
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int kBOff = BM * kRowBytes;
-  static_assert(NA * RPC * NW == BM && NB * RPC * NW == BN, "copies must tile the slab");
+  static_assert(NA * kRPC * NW == BM && NB * kRPC * NW == BN, "copies must tile the slab");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * NL < 64, "vmcnt range");
-  static_assert(KSTEPS % 2 == 0, "operand registers alternate between two sets");
+  static_assert(US % 2 == 0, "operand registers alternate between two sets");
+  static_assert(NSTAGE * kStageBytes <= 160 * 1024, "LDS");
 
   __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes];
-  __shared__ uint32_t sh_word;
 
   Tile tl;
   int slot = 0, agent = 0;
   const int role = decode_block(p, tl, slot, agent);
   if (role == kRoleNone) return;
   if (role == kRoleRelease) {
-    if (MODE == kModeFused) release_chunk(p, slot, agent, &sh_word);
+    // the release role never touches the stages: its one shared word lives there
+    if (MODE == kModeFused) release_chunk(p, slot, agent, (uint32_t *)lds);
     return;
   }
 
   Trk trk;
   if (MODE == kModeFused) trk = trk_open(p);   // reads gen now; used when the tile is done
+  if (p.stagger_groups > 1) stagger_start(p);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -304,21 +326,21 @@ void gemm_tile_kernel(const Plan p) {
   const int col_hi = col_lo + p.W;
   const int n0 = col_lo + tl.nj * BN;
 
-  // ---- global -> LDS copy addressing.  Copy q of this wavefront fills RPC LDS rows (1 KiB):
-  // lane l lands in row l / CPR, position l % CPR, so it must fetch chunk (l % CPR) ^ swz(row).
-  const int cp_row = lane / CPR;
+  // ---- global -> LDS copy addressing.  Copy q of this wavefront fills 8 LDS rows (1 KiB):
+  // lane l lands in row l / 8, position l % 8, so it must fetch chunk (l % 8) ^ swz(row).
+  const int cp_row = lane / kCPR;
   uint32_t offA[NA], offB[NB];                   // byte offsets, rows clamped into range
   int chunkA[NA], chunkB[NB];                    // the k-chunk each copy fetches
 #pragma unroll
   for (int q = 0; q < NA; ++q) {
-    const int r = wave * (BM / NW) + q * RPC + cp_row;
-    chunkA[q] = (lane % CPR) ^ swz<CPR>(r);
+    const int r = wave * (BM / NW) + q * kRPC + cp_row;
+    chunkA[q] = (lane % kCPR) ^ swz(r);
     offA[q] = (uint32_t)((min(m0 + r, p.M - 1) * p.lda + chunkA[q] * 8) * 2);
   }
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
-    const int r = wave * (BN / NW) + q * RPC + cp_row;
-    chunkB[q] = (lane % CPR) ^ swz<CPR>(r);
+    const int r = wave * (BN / NW) + q * kRPC + cp_row;
+    chunkB[q] = (lane % kCPR) ^ swz(r);
     offB[q] = (uint32_t)((min(n0 + r, col_hi - 1) * p.ldb + chunkB[q] * 8) * 2);
   }
   const int ldsA_w = wave * (BM / NW) * kRowBytes;            // this wavefront's rows, stage 0
@@ -326,129 +348,143 @@ void gemm_tile_kernel(const Plan p) {
 
   // The copies are issued as inline assembly: the compiler would otherwise wait for every
   // outstanding global->LDS copy (vmcnt(0)) before any LDS read, which defeats the prefetch.
-  // Waits for them are therefore explicit (s_waitcnt below).
+  // Waits for them are therefore explicit (s_waitcnt below).  Copies [q0, q1) of the slab's
+  // NA + NB are issued by one call, so that a slab's copies can be spread over its micro-steps
+  // (all eight wavefronts issuing all of theirs at once stalls them on the memory pipeline).
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
-  auto issue_slab = [&](int kt, int stage) {
-    const char *a = (const char *)p.A + (int64_t)kt * (BK * 2);
-    const char *b = (const char *)p.B + (int64_t)kt * (BK * 2);
+  auto issue_copies = [&](int kt, int stage, int q0, int q1) {
+    const char *a = (const char *)p.A + (int64_t)kt * (kBK * 2);
+    const char *b = (const char *)p.B + (int64_t)kt * (kBK * 2);
     const uint32_t dst = lds_base + stage * kStageBytes;
 #pragma unroll
     for (int q = 0; q < NA; ++q)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :
-                   : "s"(dst + ldsA_w + q * 1024), "v"(offA[q]), "s"(a)
-                   : "memory");
+      if (q >= q0 && q < q1)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(dst + ldsA_w + q * 1024), "v"(offA[q]), "s"(a)
+                     : "memory");
 #pragma unroll
     for (int q = 0; q < NB; ++q)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :
-                   : "s"(dst + ldsB_w + q * 1024), "v"(offB[q]), "s"(b)
-                   : "memory");
+      if (NA + q >= q0 && NA + q < q1)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(dst + ldsB_w + q * 1024), "v"(offB[q]), "s"(b)
+                     : "memory");
   };
+  auto issue_slab = [&](int kt, int stage) { issue_copies(kt, stage, 0, NL); };
 
-  // ---- MFMA operand addressing: lane reads row (lane & 31) of a 32-row block, k-chunk
-  // 2*kk + (lane >> 5) of k-step kk.
-  const int fr = lane & 31, fh = lane >> 5, fs = swz<CPR>(fr);
-  int fragA[KSTEPS], fragB[KSTEPS];
+  // ---- MFMA operand addressing (v_mfma_f32_16x16x32_bf16): lane reads row (lane & 15) of a
+  // 16-row block, k-chunk 4*kk + (lane >> 4) of k-step kk.
+  const int fr = lane & 15, fq = lane >> 4, fs = swz(fr);
+  int fragA[KS], fragB[KS];
 #pragma unroll
-  for (int kk = 0; kk < KSTEPS; ++kk) {
-    const int pos = ((2 * kk + fh) ^ fs) * 16;
+  for (int kk = 0; kk < KS; ++kk) {
+    const int pos = ((4 * kk + fq) ^ fs) * 16;
     fragA[kk] = (wm * WM + fr) * kRowBytes + pos;
     fragB[kk] = kBOff + (wn * WN + fr) * kRowBytes + pos;
   }
 
-  const int nkf = p.K / BK;                      // full slabs
-  const int ktail = p.K - nkf * BK;              // leftover elements of K (a multiple of 8)
+  const int nkf = p.K / kBK;                     // full slabs
+  const int ktail = p.K - nkf * kBK;             // leftover elements of K (a multiple of 8)
 
   // NSTAGE-1 slabs are always in flight.  Past the last slab the copies are repeated into
   // stages nobody reads any more, so every wait below is for the same number of younger copies.
   if (nkf > 0) issue_slab(0, 0);
 
   // ---- accumulators start from the incoming partial (fused) or zero.
-  // Element 4*g + e of block (i, j) is row 8*g + 4*(lane>>5) + e, column lane & 31 of the
-  // block: per register, 32 lanes cover 128 contiguous bytes of one output row.  All lanes
-  // share one 32-bit offset; the row of each register is folded into a scalar base.
+  // Block (i, j), element e of this lane: row 16*i + (lane & 15), column 16*j + 4*(lane >> 4) + e
+  // of the wavefront tile.  Per 16-byte access 4 lanes cover 64 contiguous bytes of a row.
   const bool store_only = (MODE == kModeGemm) || ((p.flags & kFlagStep0StoreOnly) && tl.s == 0);
   const bool to_fwd = (MODE == kModeFused) && (p.flags & kFlagFwdDirect) && tl.c != p.own;
   const int rw0 = m0 + wm * WM, cw0 = n0 + wn * WN;          // wavefront tile origin (uniform)
   const bool full = (rw0 + WM <= p.M) && (cw0 + WN <= col_hi);
-  const int64_t ld_in = p.ldr;
-  const uint32_t in_voff = (uint32_t)((4 * fh * ld_in + fr) * 4);
-  f32x16 acc[FM][FN];
+  const int lrow = rw0 + fr, lcol = cw0 + 4 * fq;            // this lane's row / first column, block (0,0)
+  f32x4 acc[FM][FN];
+  {
+    const int64_t ld_in = p.ldr;
+    const float *in_lane = p.R + (int64_t)lrow * ld_in + lcol;
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float v = 0.f;
-        if (MODE == kModeFused && !store_only) {
-          const int rr = i * 32 + 8 * (e >> 2) + (e & 3);         // + 4*fh per lane
-          const char *sb = (const char *)(p.R + (int64_t)(rw0 + rr) * ld_in + cw0 + j * 32);
-          if (full || (rw0 + rr + 4 * fh < p.M && cw0 + j * 32 + fr < col_hi))
-            v = __builtin_nontemporal_load((const float *)(sb + in_voff));
-        }
-        acc[i][j][e] = v;
+      for (int j = 0; j < FN; ++j) {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (MODE == kModeFused && !store_only)
+          if (full || (lrow + 16 * i < p.M && lcol + 16 * j < col_hi))
+            v = __builtin_nontemporal_load((const f32x4 *)(in_lane + (int64_t)(16 * i) * ld_in + 16 * j));
+        acc[i][j] = v;
       }
+  }
 
   if (nkf > 0) {
 #pragma unroll
     for (int st = 1; st < NSTAGE - 1; ++st) issue_slab(min(st, nkf - 1), st);
   }
 
-  // Two sets of operand registers: k-step kk uses set kk & 1, and is read from LDS while the
-  // products of k-step kk-1 are issued.
-  bf16x8 fa[2][FM], fb[2][FN];
-  auto read_frags = [&](int kk, int stage_off) {
+  // Two sets of operand registers.  Micro-step u = (k-step kk, row pass h) reads FMH row blocks
+  // of A (set u & 1) and, on the first pass of a k-step, the FN column blocks of B (set kk & 1),
+  // while the products of micro-step u-1 are issued.
+  bf16x8 fa[2][FMH], fb[2][FN];
+  auto read_u = [&](int u, int stage_off) {
+    const int kk = u / MH, h = u % MH;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
-      fa[kk & 1][i] = *(const bf16x8 *)(lds + stage_off + fragA[kk] + i * 32 * kRowBytes);
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-      fb[kk & 1][j] = *(const bf16x8 *)(lds + stage_off + fragB[kk] + j * 32 * kRowBytes);
-  };
-  auto mfma_step = [&](int set) {
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FMH; ++i)
+      fa[u & 1][i] = *(const bf16x8 *)(lds + stage_off + fragA[kk] + (h * FMH + i) * 16 * kRowBytes);
+    if (h == 0) {
 #pragma unroll
       for (int j = 0; j < FN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+        fb[kk & 1][j] = *(const bf16x8 *)(lds + stage_off + fragB[kk] + j * 16 * kRowBytes);
+    }
+  };
+  auto mfma_u = [&](int u) {
+    const int kk = u / MH, h = u % MH;
+#pragma unroll
+    for (int i = 0; i < FMH; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        acc[h * FMH + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[kk & 1][j], fa[u & 1][i],
+                                                                      acc[h * FMH + i][j], 0, 0, 0);
   };
 
   // ---- main loop: slab kt is multiplied while the next NSTAGE-1 slabs are in flight.  The
-  // products of a slab's last k-step are issued after the next barrier, under the next slab's
-  // first LDS reads.
+  // products of a slab's last micro-step are issued after the next barrier, under the next
+  // slab's first LDS reads.
   constexpr int kWaitSlab = wait_vm((NSTAGE - 2) * NL);
   if (nkf > 0) {
     __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the incoming partial) landed
     __builtin_amdgcn_s_barrier();
     issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
-    read_frags(0, 0);
+    read_u(0, 0);
 #pragma unroll
-    for (int kk = 1; kk < KSTEPS; ++kk) {
-      read_frags(kk, 0);
-      mfma_step((kk - 1) & 1);
+    for (int u = 1; u < US; ++u) {
+      read_u(u, 0);
+      mfma_u(u - 1);
     }
     int stage = 1;
     for (int kt = 1; kt < nkf; ++kt) {
       const int so = stage * kStageBytes;
+      const int kt_next = min(kt + NSTAGE - 1, nkf - 1);
+      const int st_next = stage >= 1 ? stage - 1 : NSTAGE - 1;
       asm volatile("" ::: "memory");               // LDS reads above stay above the barrier
       __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);   // own copies of slab kt landed, own LDS reads done
       __builtin_amdgcn_s_barrier();                // everyone's; all are done with the stage refilled next
-      issue_slab(min(kt + NSTAGE - 1, nkf - 1), stage >= 1 ? stage - 1 : NSTAGE - 1);
 #pragma unroll
-      for (int kk = 0; kk < KSTEPS; ++kk) {
-        read_frags(kk, so);
-        mfma_step((kk - 1) & 1);                   // kk == 0: last k-step of slab kt-1
+      for (int u = 0; u < US; ++u) {
+        read_u(u, so);
+        if (u < SPREAD) issue_copies(kt_next, st_next, u * NL / SPREAD, (u + 1) * NL / SPREAD);
+        mfma_u((u + US - 1) % US);                 // u == 0: last micro-step of slab kt-1
       }
 #pragma unroll
-      for (int kk = 0; kk < KSTEPS; ++kk) {
-        __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FM + FN, 0);
-        __builtin_amdgcn_sched_group_barrier(kSchedMfma, FM * FN, 0);
+      for (int kk = 0; kk < KS; ++kk) {
+        __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH + FN, 0);
+        __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
+        if (MH == 2) {
+          __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
+          __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
+        }
       }
       stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     }
-    mfma_step((KSTEPS - 1) & 1);
+    mfma_u(US - 1);
     __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies
   }
   asm volatile("" ::: "memory");
@@ -456,7 +492,7 @@ void gemm_tile_kernel(const Plan p) {
   if (ktail) {
     // ragged end of K: through registers, chunks past K zeroed, into stage 0
     __syncthreads();
-    const int64_t kb = (int64_t)nkf * (BK * 2);
+    const int64_t kb = (int64_t)nkf * (kBK * 2);
     const uint4 zero = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
@@ -472,35 +508,29 @@ void gemm_tile_kernel(const Plan p) {
     }
     __syncthreads();
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk)
-      if (kk * 16 < ktail) {
-        read_frags(kk, 0);
-        mfma_step(kk & 1);
+    for (int u = 0; u < US; ++u)
+      if ((u / MH) * 32 < ktail) {
+        read_u(u, 0);
+        mfma_u(u);
       }
   }
 
-  // ---- epilogue: one agent-scope store per accumulator register
-  float *out_base;        // origin of this wavefront's tile in the output
+  // ---- epilogue: one 16-byte agent-scope store per block
+  float *out_lane;        // this lane's element of block (0, 0) in the output
   int64_t ld_out;
   if (to_fwd) {
     ld_out = p.W;
-    out_base = p.fwd + ((int64_t)tl.s * p.M + rw0) * p.W + (cw0 - col_lo);
+    out_lane = p.fwd + ((int64_t)tl.s * p.M + lrow) * p.W + (lcol - col_lo);
   } else {
     ld_out = (MODE == kModeGemm) ? p.ldc : p.ldr;
-    out_base = p.R + (int64_t)rw0 * ld_out + cw0;
+    out_lane = p.R + (int64_t)lrow * ld_out + lcol;
   }
-  const uint32_t out_voff = (uint32_t)((4 * fh * ld_out + fr) * 4);
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int rr = i * 32 + 8 * (e >> 2) + (e & 3);
-        char *sb = (char *)(out_base + (int64_t)rr * ld_out + j * 32);
-        if (full || (rw0 + rr + 4 * fh < p.M && cw0 + j * 32 + fr < col_hi))
-          store_agent((float *)(sb + out_voff), acc[i][j][e]);
-      }
+      if (full || (lrow + 16 * i < p.M && lcol + 16 * j < col_hi))
+        store_agent((f32x4 *)(out_lane + (int64_t)(16 * i) * ld_out + 16 * j), acc[i][j]);
 
   if (MODE == kModeFused) track_tile(p, trk, tl.c);
 }
