@@ -94,13 +94,16 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
     if ((int64_t)p->M * p->lda >= (1ll << 31) || (int64_t)p->N * p->ldb >= (1ll << 31))
       return T3_ERR_UNSUPPORTED;
   }
+  // kernels address R, C and a forward slot with 32-bit byte offsets
   if (need & kNeedR) {
     if (p->ldr < p->N) return T3_ERR_BAD_SHAPE;
     if (p->ldr % 4 || W % 4 || !aligned16(R)) return T3_ERR_ALIGN;
+    if ((int64_t)p->M * p->ldr * 4 >= (1ll << 32)) return T3_ERR_UNSUPPORTED;
   }
   if (need & kNeedC) {
     if (p->ldc < p->N) return T3_ERR_BAD_SHAPE;
     if (p->ldc % 4 || W % 4 || !aligned16(C)) return T3_ERR_ALIGN;
+    if ((int64_t)p->M * p->ldc * 4 >= (1ll << 32)) return T3_ERR_UNSUPPORTED;
   }
   if ((need & kNeedFwd) && fwd && !aligned16(fwd)) return T3_ERR_ALIGN;
 

@@ -18,6 +18,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef T3_MH
+#define T3_MH 4
+#endif
 #ifndef T3_AGENTS
 #define T3_AGENTS 32          // release workgroups per forwarded chunk (multiple of 8)
 #endif
@@ -185,6 +188,21 @@ __device__ inline void store_agent(float *p, float v) {
 __device__ inline void store_agent(f32x4 *p, f32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
+// Tile results and the incoming partial are accessed through buffer instructions: uniform
+// descriptor, 32-bit byte offset of the lane, uniform offset of the block.  They are issued as
+// compiler builtins, not inline assembly, so that the compiler keeps the required distance
+// between an MFMA and a store that reads its result.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+constexpr int kAuxNt = 2, kAuxSc1 = 16;     // cache-policy bits of the buffer builtins on gfx94x/gfx950
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ inline void store_agent(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t blk_off, f32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)lane_off, (int)blk_off, kAuxSc1);
+}
+__device__ inline f32x4 load_stream(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t blk_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)blk_off, kAuxNt));
+}
 
 // ---------------------------------------------------------------------------------------------
 // Track & trigger (Sec. 4.2).  Called by all threads of a workgroup after the tile's stores
@@ -273,34 +291,65 @@ constexpr int kRPC = 8;               // rows filled by one 1-KiB copy
 // sched_group_barrier masks
 constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100;
 
+// Instruction order of one MFMA k-step: the operand reads of each of its MH row passes
+// (EXTRA more reads in the first), each followed by that pass's FMH * FN products.
+template <int MH, int FMH, int FN, int EXTRA>
+__device__ inline void sched_kstep() {
+  __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH + FN + EXTRA, 0);
+  __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
+  if constexpr (MH >= 2) {
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
+  }
+  if constexpr (MH == 4) {
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
+  }
+}
+
+constexpr int kRingSlots = 4;         // 1-KiB slots per wavefront of the incoming-partial ring
+
 // WAVES_M x WAVES_N wavefronts per workgroup, each producing a (BM/WAVES_M) x (BN/WAVES_N)
 // block of the tile out of 16 x 16 MFMA blocks; NSTAGE LDS stages, NSTAGE-1 slabs in flight.
 //
 // The products are formed transposed (the B rows go in as the MFMA's first operand, the A rows
 // as its second), so that a lane ends up holding, per block, one output row and FOUR
-// CONSECUTIVE COLUMNS: the incoming partial is read and the sum written with 16-byte accesses,
-// 32 of each per wavefront for a 128 x 64 wavefront tile, all in flight together.
+// CONSECUTIVE COLUMNS: the incoming partial is read and the sum written with 16-byte accesses.
+//
+// Fused kernels with two stages stream the incoming partial in DURING the main loop (a compute
+// unit pulls data that is not in its L2 at only ~11 bytes/clock, so fetching a tile's 256 KiB
+// up front would idle the matrix cores for a third of the tile's time): each iteration a
+// wavefront copies one or two of its own 16 x 16 blocks global -> LDS into a private ring of
+// four 1-KiB slots, in the accumulator layout, behind the slab copies in issue order; two
+// iterations later the block has landed (it is older than the slab copies the next wait is
+// for), is read back and added to its accumulators.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2)))
 void gemm_tile_kernel(const Plan p) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wavefront tile
   constexpr int FM = WM / 16, FN = WN / 16;     // 16x16 MFMA blocks per wavefront
-  constexpr int MH = FM > 4 ? 2 : 1;            // a k-step is taken in MH passes over the rows,
+  constexpr int MH = FM > 4 ? T3_MH : 1;        // a k-step is taken in MH passes over the rows,
   constexpr int FMH = FM / MH;                  //   FMH row blocks each, to bound operand registers
   constexpr int KS = kBK / 32;                  // MFMA k-steps per slab
   constexpr int US = KS * MH;                   // micro-steps (row pass of a k-step) per slab
   constexpr int NA = BM / kRPC / NW, NB = BN / kRPC / NW;   // copies per wavefront per slab
   constexpr int NL = NA + NB;
-  constexpr int SPREAD = US >= 4 ? 2 : 1;       // micro-steps over which a slab's copies are issued
+  constexpr int NBLK = FM * FN;
+  constexpr bool STREAM = (MODE == kModeFused) && NSTAGE == 2;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int kBOff = BM * kRowBytes;
+  constexpr int kRingBytes = STREAM ? NW * kRingSlots * 1024 : 0;
   static_assert(NA * kRPC * NW == BM && NB * kRPC * NW == BN, "copies must tile the slab");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * NL < 64, "vmcnt range");
-  static_assert(US % 2 == 0, "operand registers alternate between two sets");
-  static_assert(NSTAGE * kStageBytes <= 160 * 1024, "LDS");
+  static_assert(KS == 2, "the loop body is written as two k-steps");
+  static_assert(NL % MH == 0, "a slab's copies are split evenly over the first k-step's passes");
+  static_assert((FN & (FN - 1)) == 0, "block index -> (row block, column block) by shifts");
+  static_assert(NSTAGE * kStageBytes + kRingBytes <= 160 * 1024, "LDS");
 
-  __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes + kRingBytes];
 
   Tile tl;
   int slot = 0, agent = 0;
@@ -330,18 +379,18 @@ void gemm_tile_kernel(const Plan p) {
   // lane l lands in row l / 8, position l % 8, so it must fetch chunk (l % 8) ^ swz(row).
   const int cp_row = lane / kCPR;
   uint32_t offA[NA], offB[NB];                   // byte offsets, rows clamped into range
-  int chunkA[NA], chunkB[NB];                    // the k-chunk each copy fetches
+  auto chunk_of = [&](int rows_per_wave, int q) {  // the k-chunk copy q of this lane fetches
+    return (lane % kCPR) ^ swz(wave * rows_per_wave + q * kRPC + cp_row);
+  };
 #pragma unroll
   for (int q = 0; q < NA; ++q) {
     const int r = wave * (BM / NW) + q * kRPC + cp_row;
-    chunkA[q] = (lane % kCPR) ^ swz(r);
-    offA[q] = (uint32_t)((min(m0 + r, p.M - 1) * p.lda + chunkA[q] * 8) * 2);
+    offA[q] = (uint32_t)((min(m0 + r, p.M - 1) * p.lda + chunk_of(BM / NW, q) * 8) * 2);
   }
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
     const int r = wave * (BN / NW) + q * kRPC + cp_row;
-    chunkB[q] = (lane % kCPR) ^ swz(r);
-    offB[q] = (uint32_t)((min(n0 + r, col_hi - 1) * p.ldb + chunkB[q] * 8) * 2);
+    offB[q] = (uint32_t)((min(n0 + r, col_hi - 1) * p.ldb + chunk_of(BN / NW, q) * 8) * 2);
   }
   const int ldsA_w = wave * (BM / NW) * kRowBytes;            // this wavefront's rows, stage 0
   const int ldsB_w = kBOff + wave * (BN / NW) * kRowBytes;
@@ -399,21 +448,95 @@ void gemm_tile_kernel(const Plan p) {
   const int rw0 = m0 + wm * WM, cw0 = n0 + wn * WN;          // wavefront tile origin (uniform)
   const bool full = (rw0 + WM <= p.M) && (cw0 + WN <= col_hi);
   const int lrow = rw0 + fr, lcol = cw0 + 4 * fq;            // this lane's row / first column, block (0,0)
+  // Streaming kernels take the incoming partial in during the main loop, two blocks (a "pair")
+  // at a time, if K is long enough for all NBLK / 2 pairs; otherwise it is loaded here.
+  constexpr int NPAIR = NBLK / 2;
+  static_assert(FN % 2 == 0, "pairs");
+  const bool streaming = STREAM && !store_only && nkf >= NPAIR;
+  const int n_pre = streaming ? 0 : NBLK;
+  // Every access to R, C or a forward slot is (uniform base) + (32-bit byte offset of the lane),
+  // the offset formed per block when it is needed: byte sizes of these arrays stay below 4 GiB.
   f32x4 acc[FM][FN];
   {
-    const int64_t ld_in = p.ldr;
-    const float *in_lane = p.R + (int64_t)lrow * ld_in + lcol;
+    const uint32_t ld_in = (uint32_t)p.ldr;
+    const __amdgpu_buffer_rsrc_t in_rsrc = make_rsrc(p.R, (uint32_t)p.M * ld_in * 4u);
+    const uint32_t in_lane = ((uint32_t)lrow * ld_in + (uint32_t)lcol) * 4u;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (MODE == kModeFused && !store_only)
+        if (MODE == kModeFused && !store_only && i * FN + j < n_pre)
           if (full || (lrow + 16 * i < p.M && lcol + 16 * j < col_hi))
-            v = __builtin_nontemporal_load((const f32x4 *)(in_lane + (int64_t)(16 * i) * ld_in + 16 * j));
+            v = load_stream(in_rsrc, in_lane, ((uint32_t)(16 * i) * ld_in + (uint32_t)(16 * j)) * 4u);
         acc[i][j] = v;
       }
   }
+
+  // ---- "pairs".  Global accesses that touch half a 128-byte line per row (what one 16 x 16
+  // block in the accumulator layout amounts to) run at a third of the rate of full lines, so
+  // the incoming partial and the results move in units of one PAIR = two neighbouring blocks =
+  // 16 rows x 32 columns = two instructions of 8 rows x 128 bytes each, and are transposed to
+  // and from the accumulator layout in LDS.  A pair occupies two 1-KiB slots (rows 0-7, rows
+  // 8-15); in a slot, the lane that a linear access maps to position (rp, pp) = (lane / 8,
+  // lane % 8) holds row r = rp (first slot) or rp ^ 1 (second slot), 16-byte chunk pp ^ r: with
+  // that swizzle both the linear side and the accumulator side are bank-conflict free.
+  constexpr int UJ = FN / 2;                     // pairs per row of blocks
+  struct PairLane {
+    int row[2], col[2];   // row / column (in the pair) of the linear side's two instructions
+    int acc[2];           // byte offset (in the pair's two slots) of the lane's 16 bytes of block 0 / 1
+  };
+  auto pair_lane = [](int ln) {
+    PairLane u;
+    const int rp = ln >> 3, pp = ln & 7;
+    u.row[0] = rp;
+    u.row[1] = 8 + (rp ^ 1);
+    u.col[0] = 4 * (pp ^ rp);
+    u.col[1] = 4 * (pp ^ rp ^ 1);
+    const int m = ln & 15, q = ln >> 4, h = m >> 3, r = m & 7, rq = h ? (r ^ 1) : r;
+    u.acc[0] = h * 1024 + rq * 128 + (q ^ r) * 16;
+    u.acc[1] = h * 1024 + rq * 128 + ((4 + q) ^ r) * 16;
+    return u;
+  };
+  const PairLane ul = pair_lane(lane);           // (streaming kernels only: the epilogue recomputes it)
+  const int *u_row = ul.row, *u_col = ul.col, *u_acc = ul.acc;
+
+  // ---- the incoming-partial ring (streaming kernels): four slots per wavefront, pair t in
+  // slots {0, 1} (t even) or {2, 3} (t odd).
+  char *ring = lds + NSTAGE * kStageBytes + wave * (kRingSlots * 1024);
+  int c1 = 0;                                    // incoming copies issued in the previous iteration
+  uint32_t in_u[2];                              // byte offsets of the linear side in R, rows of ldr
+#pragma unroll
+  for (int h = 0; h < 2; ++h) in_u[h] = ((uint32_t)u_row[h] * (uint32_t)p.ldr + (uint32_t)u_col[h]) * 4u;
+  auto issue_pair = [&](int t) {                 // the two copies of pair t
+    const int i = t / UJ, jj = t % UJ;
+    const int pr = rw0 + 16 * i, pc = cw0 + 32 * jj;          // pair origin (uniform)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t dst = lds_base + NSTAGE * kStageBytes + wave * (kRingSlots * 1024) +
+                           (((2 * t) & (kRingSlots - 1)) + h) * 1024;
+      const char *base = (const char *)p.R;
+      uint32_t off;
+      if (full) {
+        base += ((int64_t)pr * p.ldr + pc) * 4;
+        off = in_u[h];
+      } else {  // rows and columns past the ragged edge are clamped: what lands there is never stored
+        const int rr = min(pr + u_row[h], p.M - 1), cc = min(pc + u_col[h], col_hi - 4);
+        off = ((uint32_t)rr * (uint32_t)p.ldr + (uint32_t)cc) * 4u;
+      }
+      // the slot's previous pair has been read back (lgkmcnt) before it is overwritten
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(dst), "v"(off), "s"(base)
+                   : "memory");
+    }
+  };
+  auto add_pair = [&](int t) {                   // t is a constant wherever this is called
+    const int i = t / UJ, jj = t % UJ;
+    const char *slot = ring + ((2 * t) & (kRingSlots - 1)) * 1024;
+    acc[i][2 * jj] += *(const f32x4 *)(slot + u_acc[0]);
+    acc[i][2 * jj + 1] += *(const f32x4 *)(slot + u_acc[1]);
+  };
 
   if (nkf > 0) {
 #pragma unroll
@@ -447,45 +570,90 @@ void gemm_tile_kernel(const Plan p) {
 
   // ---- main loop: slab kt is multiplied while the next NSTAGE-1 slabs are in flight.  The
   // products of a slab's last micro-step are issued after the next barrier, under the next
-  // slab's first LDS reads.
+  // slab's first LDS reads.  An iteration is: wait + barrier; k-step 0, with the next slab's
+  // copies spread over its row passes; the incoming-partial work, if any; k-step 1.
+  //
+  // Streaming schedule (pairs must be named by constants to stay in registers, so the loop is
+  // laid out as NPAIR phases of `stride` iterations, one copy of the loop body per phase):
+  // iteration 0 issues pair 0; the first iteration of phase t = 1 .. NPAIR-1 adds pair t-2 and
+  // issues pair t; the first two iterations after the phases add the last two pairs; what the
+  // loop did not get to is added after it.  A pair is added two or more iterations after it
+  // was issued: by then it has landed, being older than slab copies already waited for.
   constexpr int kWaitSlab = wait_vm((NSTAGE - 2) * NL);
   if (nkf > 0) {
-    __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the incoming partial) landed
+    __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the blocks loaded up front) landed
     __builtin_amdgcn_s_barrier();
     issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
+    if (STREAM && streaming) {
+      issue_pair(0);
+      c1 = 2;
+    }
     read_u(0, 0);
 #pragma unroll
     for (int u = 1; u < US; ++u) {
       read_u(u, 0);
       mfma_u(u - 1);
     }
-    int stage = 1;
-    for (int kt = 1; kt < nkf; ++kt) {
+    int stage = 1, kt = 1;
+    auto iteration = [&](auto &&stream_ops) {      // one slab; stream_ops() returns copies issued
       const int so = stage * kStageBytes;
       const int kt_next = min(kt + NSTAGE - 1, nkf - 1);
       const int st_next = stage >= 1 ? stage - 1 : NSTAGE - 1;
       asm volatile("" ::: "memory");               // LDS reads above stay above the barrier
-      __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);   // own copies of slab kt landed, own LDS reads done
+      // own copies of slab kt landed (the c1 younger incoming copies may still fly), own LDS reads done
+      if (STREAM) {
+        if (c1) __builtin_amdgcn_s_waitcnt(wait_vm(2) & kWaitLgkm0);
+        else __builtin_amdgcn_s_waitcnt(wait_vm(0) & kWaitLgkm0);
+      } else {
+        __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);
+      }
       __builtin_amdgcn_s_barrier();                // everyone's; all are done with the stage refilled next
 #pragma unroll
-      for (int u = 0; u < US; ++u) {
+      for (int u = 0; u < MH; ++u) {               // k-step 0
         read_u(u, so);
-        if (u < SPREAD) issue_copies(kt_next, st_next, u * NL / SPREAD, (u + 1) * NL / SPREAD);
+        issue_copies(kt_next, st_next, u * NL / MH, (u + 1) * NL / MH);
         mfma_u((u + US - 1) % US);                 // u == 0: last micro-step of slab kt-1
       }
+      sched_kstep<MH, FMH, FN, 0>();
+      if (STREAM) c1 = stream_ops();
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
-        __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH + FN, 0);
-        __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
-        if (MH == 2) {
-          __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
-          __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
-        }
+      for (int u = MH; u < US; ++u) {              // k-step 1
+        read_u(u, so);
+        mfma_u(u - 1);
       }
+      sched_kstep<MH, FMH, FN, 0>();
       stage = stage == NSTAGE - 1 ? 0 : stage + 1;
+      ++kt;
+    };
+    int pairs_added = 0, pairs_issued = (STREAM && streaming) ? 1 : 0;
+    if (STREAM && streaming) {
+      const int stride = (nkf - 1) / (NPAIR - 1);
+#pragma unroll
+      for (int t = 1; t < NPAIR; ++t)
+        for (int s = 0; s < stride; ++s)
+          iteration([&]() {
+            if (s) return 0;
+            if (t >= 2) add_pair(t - 2);
+            issue_pair(t);
+            return 2;
+          });
+      pairs_added = NPAIR - 2;
+      pairs_issued = NPAIR;
     }
+    for (int r = (STREAM && streaming) ? 0 : 2; kt < nkf; ++r)
+      iteration([&]() {
+        if (r == 0) add_pair(NPAIR - 2);
+        if (r == 1) add_pair(NPAIR - 1);
+        if (r < 2) ++pairs_added;
+        return 0;
+      });
     mfma_u(US - 1);
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies and the last pairs
+    if (STREAM) {
+#pragma unroll
+      for (int t = 0; t < NPAIR; ++t)
+        if (t >= pairs_added && t < pairs_issued) add_pair(t);
+    }
   }
   asm volatile("" ::: "memory");
 
@@ -497,40 +665,69 @@ void gemm_tile_kernel(const Plan p) {
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
       uint4 v = zero;
-      if (chunkA[q] * 8 < ktail) v = *(const uint4 *)((const char *)p.A + kb + offA[q]);
+      if (chunk_of(BM / NW, q) * 8 < ktail) v = *(const uint4 *)((const char *)p.A + kb + offA[q]);
       *(uint4 *)(lds + ldsA_w + q * 1024 + lane * 16) = v;
+      if (q % 2 == 1) __builtin_amdgcn_sched_barrier(0);   // two loads in flight, not all: registers
     }
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       uint4 v = zero;
-      if (chunkB[q] * 8 < ktail) v = *(const uint4 *)((const char *)p.B + kb + offB[q]);
+      if (chunk_of(BN / NW, q) * 8 < ktail) v = *(const uint4 *)((const char *)p.B + kb + offB[q]);
       *(uint4 *)(lds + ldsB_w + q * 1024 + lane * 16) = v;
+      if (q % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
+    // both k-steps, whatever ktail is: the zeroed chunks add nothing
 #pragma unroll
-    for (int u = 0; u < US; ++u)
-      if ((u / MH) * 32 < ktail) {
-        read_u(u, 0);
-        mfma_u(u);
-      }
+    for (int u = 0; u < US; ++u) {
+      read_u(u, 0);
+      mfma_u(u);
+    }
   }
 
   // ---- epilogue: one 16-byte agent-scope store per block
-  float *out_lane;        // this lane's element of block (0, 0) in the output
-  int64_t ld_out;
+  const float *out_base;  // uniform: R, C, or the chunk's forward slot
+  uint32_t ld_out;
+  int col_org;            // column the base's rows start at
   if (to_fwd) {
-    ld_out = p.W;
-    out_lane = p.fwd + ((int64_t)tl.s * p.M + lrow) * p.W + (lcol - col_lo);
+    ld_out = (uint32_t)p.W;
+    out_base = p.fwd + (int64_t)tl.s * p.M * p.W;
+    col_org = col_lo;
   } else {
-    ld_out = (MODE == kModeGemm) ? p.ldc : p.ldr;
-    out_lane = p.R + (int64_t)lrow * ld_out + lcol;
+    ld_out = (uint32_t)((MODE == kModeGemm) ? p.ldc : p.ldr);
+    out_base = p.R;
+    col_org = 0;
   }
+  const __amdgpu_buffer_rsrc_t out_rsrc = make_rsrc(out_base, (uint32_t)p.M * ld_out * 4u);
+  // Pair by pair through LDS (the stages are free now; each wavefront uses 4 KiB of its own):
+  // written in the accumulator layout, read back linearly, stored as 8 rows x 128 bytes.
+  {
+  __syncthreads();
+  char *scr = lds + wave * (kRingSlots * 1024);
+  int lane_e = lane;                             // recomputed here rather than kept through the main loop
+  asm volatile("" : "+v"(lane_e));
+  const PairLane ue = pair_lane(lane_e);
+  const int *u_row = ue.row, *u_col = ue.col, *u_acc = ue.acc;
+  uint32_t out_u[2];
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+  for (int h = 0; h < 2; ++h)
+    out_u[h] = ((uint32_t)(rw0 + u_row[h]) * ld_out + (uint32_t)(cw0 - col_org + u_col[h])) * 4u;
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-      if (full || (lrow + 16 * i < p.M && lcol + 16 * j < col_hi))
-        store_agent((f32x4 *)(out_lane + (int64_t)(16 * i) * ld_out + 16 * j), acc[i][j]);
+  for (int t = 0; t < NBLK / 2; ++t) {
+    const int i = t / UJ, jj = t % UJ;
+    char *slot = scr + ((2 * t) & (kRingSlots - 1)) * 1024;
+    *(f32x4 *)(slot + u_acc[0]) = acc[i][2 * jj];
+    *(f32x4 *)(slot + u_acc[1]) = acc[i][2 * jj + 1];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane * 16);
+      if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
+        store_agent(out_rsrc, out_u[h], ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u, v);
+    }
+    // keep the scheduler from running many pairs ahead: it would park their values in registers
+    if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+  }
+  }
 
   if (MODE == kModeFused) track_tile(p, trk, tl.c);
 }
