@@ -176,6 +176,8 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // forwarded chunks those tiles complete
   const int64_t done_chunks = tpc > 0 ? q.limit / tpc : 0;
   q.expected_done = (int32_t)(q.limit + q.agents * (done_chunks < p->tp - 1 ? done_chunks : p->tp - 1));
+  q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
+  q.resident = (int32_t)resident;
   return T3_OK;
 }
 
@@ -188,13 +190,12 @@ t3_status launched(void) {
   return T3_OK;
 }
 
-inline unsigned grid_size(const t3k::Plan &q) {
-  return (unsigned)((int64_t)q.tpc * q.P + (int64_t)q.agents * (q.P - 1));
-}
+inline unsigned grid_size(const t3k::Plan &q) { return (unsigned)q.total_blocks; }
 
 template <int MODE>
 void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
-  const dim3 grid(grid_size(q));
+  // persistent workgroups: as many as the chip holds at once, each walking the grid positions
+  const dim3 grid((unsigned)(q.total_blocks < q.resident ? q.total_blocks : q.resident));
   // K-slabs of 64 everywhere.  256 x 256: 8 wavefronts of 128 x 64, two 64-KiB stages; the
   // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
   // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.

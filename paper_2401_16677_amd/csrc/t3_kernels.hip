@@ -63,7 +63,9 @@ struct Plan {
   int32_t Mt, Wt, tpc;
   int32_t xcd_nbm, xcd_bmk, xcd_bnk;   // XCD grouping of a stage's tiles; xcd_nbm == 0: none
   int32_t agents, lag, rows_per_agent; // release workgroups per chunk, their lag in stages
-  int32_t expected_done;               // workgroups of this launch that do work
+  int32_t expected_done;               // grid positions of this launch that do work
+  int32_t total_blocks;                // grid positions (tiles and release work) of the launch
+  int32_t resident;                    // tile workgroups the chip holds at once
   int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
   uint32_t flags;
 };
@@ -142,8 +144,7 @@ __device__ inline bool decode_tile(const Plan &p, int s, int j, Tile &tl) {
 // Grid layout: the tiles of stage 0, 1, ... in order; after the tiles of stage s come the
 // `agents` release workgroups of forward slot s - lag (a chunk whose tiles were all dispatched
 // at least `lag` stages earlier); slots not served that way follow the last stage.
-__device__ inline int decode_block(const Plan &p, Tile &tl, int &slot, int &agent) {
-  const int b = blockIdx.x;
+__device__ inline int decode_block(const Plan &p, int b, Tile &tl, int &slot, int &agent) {
   int base = 0;
   for (int s = 0; s < p.P; ++s) {
     if (b < base + p.tpc) return decode_tile(p, s, b - base, tl) ? kRoleTile : kRoleNone;
@@ -210,9 +211,15 @@ __device__ inline f32x4 load_stream(__amdgpu_buffer_rsrc_t r, uint32_t lane_off,
 // acknowledged (vmcnt == 0 in every wavefront, then the barrier) the tile is counted.  A
 // device-scope release fence instead would write back the whole L2 for every tile and costs
 // several times the reduction itself.
+__device__ inline void track_count(const Plan &p, const Trk &t, int c);
 __device__ inline void track_tile(const Plan &p, const Trk &t, int c) {
   __builtin_amdgcn_s_waitcnt(kWaitAll);
   __syncthreads();
+  track_count(p, t, c);
+}
+// The counting itself, once every wavefront's stores of the tile are known to be acknowledged
+// and a barrier has passed.
+__device__ inline void track_count(const Plan &p, const Trk &t, int c) {
   if (threadIdx.x == 0) {
     // both increments are in flight together: one round trip at the end of a tile, not two
     const uint32_t old = __hip_atomic_fetch_add(&t.counter[c], 1u, __ATOMIC_RELAXED,
@@ -351,24 +358,39 @@ void gemm_tile_kernel(const Plan p) {
 
   __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes + kRingBytes];
 
-  Tile tl;
-  int slot = 0, agent = 0;
-  const int role = decode_block(p, tl, slot, agent);
-  if (role == kRoleNone) return;
-  if (role == kRoleRelease) {
-    // the release role never touches the stages: its one shared word lives there
-    if (MODE == kModeFused) release_chunk(p, slot, agent, (uint32_t *)lds);
-    return;
-  }
-
+  // Persistent workgroups: workgroup w takes grid positions w, w + gridDim.x, ... in order (a
+  // position is a tile or a piece of release work).  The tracking of a finished tile is
+  // deferred into the next tile: by the first barrier of that tile's main loop every
+  // wavefront has waited for its stores (they are older than the slab copies waited for
+  // there), so the acknowledgement wait costs nothing.
   Trk trk;
-  if (MODE == kModeFused) trk = trk_open(p);   // reads gen now; used when the tile is done
+  if (MODE == kModeFused) trk = trk_open(p);   // reads gen now; used when tiles are done
   if (p.stagger_groups > 1) stagger_start(p);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  int pending_c = -1;                          // chunk of a tile whose stores are issued but not counted
+  auto flush_pending = [&]() {
+    if (MODE == kModeFused && pending_c >= 0) track_tile(p, trk, pending_c);
+    pending_c = -1;
+  };
+
+  for (int blk = blockIdx.x; blk < p.total_blocks; blk += gridDim.x) {
+  Tile tl;
+  int slot = 0, agent = 0;
+  const int role = decode_block(p, blk, tl, slot, agent);
+  if (role != kRoleTile) {
+    flush_pending();                           // release work may wait for the very tile we finished
+    // the release role never touches the stages: its one shared word lives there
+    if (role == kRoleRelease && MODE == kModeFused) {
+      __syncthreads();
+      release_chunk(p, slot, agent, (uint32_t *)lds);
+    }
+    continue;
+  }
+  __syncthreads();                             // the previous tile's epilogue is done with the LDS
 
   const int m0 = tl.mi * BM;
   const int col_lo = tl.c * p.W;                 // chunk bounds in N
@@ -452,7 +474,7 @@ void gemm_tile_kernel(const Plan p) {
   // at a time, if K is long enough for all NBLK / 2 pairs; otherwise it is loaded here.
   constexpr int NPAIR = NBLK / 2;
   static_assert(FN % 2 == 0, "pairs");
-  const bool streaming = STREAM && !store_only && nkf >= NPAIR;
+  const bool streaming = STREAM && !store_only && nkf >= NPAIR + 2;
   const int n_pre = streaming ? 0 : NBLK;
   // Every access to R, C or a forward slot is (uniform base) + (32-bit byte offset of the lane),
   // the offset formed per block when it is needed: byte sizes of these arrays stay below 4 GiB.
@@ -574,8 +596,8 @@ void gemm_tile_kernel(const Plan p) {
   // copies spread over its row passes; the incoming-partial work, if any; k-step 1.
   //
   // Streaming schedule (pairs must be named by constants to stay in registers, so the loop is
-  // laid out as NPAIR phases of `stride` iterations, one copy of the loop body per phase):
-  // iteration 0 issues pair 0; the first iteration of phase t = 1 .. NPAIR-1 adds pair t-2 and
+  // laid out as NPAIR phases, one copy of the loop body per phase): iteration 0 issues pair 0;
+  // phase t = 1 .. NPAIR-1 runs up to iteration t (nkf-2) / NPAIR, in which it adds pair t-2 and
   // issues pair t; the first two iterations after the phases add the last two pairs; what the
   // loop did not get to is added after it.  A pair is added two or more iterations after it
   // was issued: by then it has landed, being older than slab copies already waited for.
@@ -583,6 +605,10 @@ void gemm_tile_kernel(const Plan p) {
   if (nkf > 0) {
     __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the blocks loaded up front) landed
     __builtin_amdgcn_s_barrier();
+    if (MODE == kModeFused && pending_c >= 0) {    // (also older: the previous tile's stores)
+      track_count(p, trk, pending_c);
+      pending_c = -1;
+    }
     issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
     if (STREAM && streaming) {
       issue_pair(0);
@@ -627,16 +653,20 @@ void gemm_tile_kernel(const Plan p) {
     };
     int pairs_added = 0, pairs_issued = (STREAM && streaming) ? 1 : 0;
     if (STREAM && streaming) {
-      const int stride = (nkf - 1) / (NPAIR - 1);
 #pragma unroll
-      for (int t = 1; t < NPAIR; ++t)
-        for (int s = 0; s < stride; ++s)
+      for (int t = 1; t < NPAIR; ++t) {
+        const int at = (t * (nkf - 2)) / NPAIR;    // pair t is issued in iteration at: evenly spread
+        bool mine;
+        do {
+          mine = (kt == at);
           iteration([&]() {
-            if (s) return 0;
+            if (!mine) return 0;
             if (t >= 2) add_pair(t - 2);
             issue_pair(t);
             return 2;
           });
+        } while (!mine);
+      }
       pairs_added = NPAIR - 2;
       pairs_issued = NPAIR;
     }
@@ -729,7 +759,12 @@ void gemm_tile_kernel(const Plan p) {
   }
   }
 
-  if (MODE == kModeFused) track_tile(p, trk, tl.c);
+  if (MODE == kModeFused) {
+    if (nkf == 0) flush_pending();               // (no main loop ran: nothing was counted on the way)
+    pending_c = tl.c;
+  }
+  }  // grid positions
+  flush_pending();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -740,7 +775,7 @@ __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
   __shared__ uint32_t sh_word;
   Tile tl;
   int slot = 0, agent = 0;
-  const int role = decode_block(p, tl, slot, agent);
+  const int role = decode_block(p, blockIdx.x, tl, slot, agent);
   if (role == kRoleNone) return;
   if (role == kRoleRelease) {
     release_chunk(p, slot, agent, &sh_word);
