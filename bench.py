@@ -62,8 +62,10 @@ def main():
                          "(T3_FLAG_FWD_DIRECT); copy: sums are added in place and release "
                          "workgroups copy each triggered chunk to its forward slot")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--no-graph", action="store_true",
-                    help="launch the step's kernels one by one instead of replaying a HIP graph")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each step as a captured HIP graph instead of launching its kernels "
+                         "one by one (a step here is one or two kernels: back-to-back launches keep "
+                         "the queue full, a graph launch per step leaves a gap between steps)")
     args = ap.parse_args()
     args.direct = args.release == "direct"
     if args.gpus != 1:
@@ -112,7 +114,7 @@ def main():
             step()
         return g.replay
 
-    if not args.no_graph:
+    if args.graph:
         fused_step = graphed(fused_step)
         unfused_step = graphed(unfused_step)
 
@@ -174,7 +176,7 @@ def main():
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "tp": w.tp, "rank": w.rank,
                    "tile": [w.tile_m, w.tile_n],
                    "release": "direct" if args.direct else "copy",
-                   "launch": "eager" if args.no_graph else "hip_graph"},
+                   "launch": "hip_graph" if args.graph else "eager"},
         "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "unfused_ms_per_step": t_unfused * 1e3,
         "speedup_vs_unfused": t_unfused / t_fused,

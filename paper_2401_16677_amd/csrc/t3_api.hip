@@ -194,8 +194,12 @@ inline unsigned grid_size(const t3k::Plan &q) { return (unsigned)q.total_blocks;
 
 template <int MODE>
 void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
-  // persistent workgroups: as many as the chip holds at once, each walking the grid positions
-  const dim3 grid((unsigned)(q.total_blocks < q.resident ? q.total_blocks : q.resident));
+  // Persistent workgroups: as many as the chip holds at once, each walking the grid positions.
+  // With release work in the grid (default release mode) every position gets a workgroup of
+  // its own instead: a release position may have to wait for its chunk, and a persistent
+  // workgroup would sit on its later tiles meanwhile.
+  const bool persistent = q.agents == 0;
+  const dim3 grid((unsigned)(persistent && q.total_blocks > q.resident ? q.resident : q.total_blocks));
   // K-slabs of 64 everywhere.  256 x 256: 8 wavefronts of 128 x 64, two 64-KiB stages; the
   // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
   // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.

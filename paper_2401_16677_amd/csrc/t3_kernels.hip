@@ -19,7 +19,7 @@
 #include <stdint.h>
 
 #ifndef T3_MH
-#define T3_MH 4
+#define T3_MH 2
 #endif
 #ifndef T3_AGENTS
 #define T3_AGENTS 32          // release workgroups per forwarded chunk (multiple of 8)
