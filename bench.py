@@ -22,6 +22,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6     # 256 CU x 2.4 GHz x 4096 flop/clk/CU, dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by the same counters' reading of a plain copy (profiles/*_hbm_traffic.txt says how).
+# Keyed by (workload, release); None = not measured since the kernel last changed.
+MEASURED_TRAFFIC_BYTES = {}
+
 
 def algorithmic_bytes(w, direct):
     """Bytes the method must move: A and B once, incoming once, result once; the default
@@ -66,6 +71,9 @@ def main():
                     help="replay each step as a captured HIP graph instead of launching its kernels "
                          "one by one (a step here is one or two kernels: back-to-back launches keep "
                          "the queue full, a graph launch per step leaves a gap between steps)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs: launch 5 x [a "
+                         "plain device copy of the M x N fp32 buffer, the fused kernel] and exit")
     args = ap.parse_args()
     args.direct = args.release == "direct"
     if args.gpus != 1:
@@ -99,6 +107,16 @@ def main():
     def unfused_step():
         t3.t3_gemm(p, A, B, C)
         t3.t3_rs_reduce(p, C, R, fwd, track)
+
+    if args.traffic_probe:
+        # the copy (a known number of bytes each way) calibrates the counters; see profiles/
+        for _ in range(5):
+            C.copy_(R)
+            fused_step()
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": w.name, "copy_bytes_each_way": 4 * w.M * w.N,
+                          "launches": 5}))
+        return
 
     def graphed(step):
         """Capture one step (its kernels are launched on the capturing stream) and return a
@@ -159,11 +177,13 @@ def main():
     if t_mfma >= t_hbm:
         ach = w.flop / (k_avg * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+                "frac": ach / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.release))}
     else:
         ach = bytes_alg / (k_avg * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None}
+                "frac": ach / PEAK_HBM_GBS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.release))}
     roof.update(kernel="gemm_tile_kernel<%d,%d,fused>" % (w.tile_m, w.tile_n),
                 kernel_ms_avg=k_avg, kernel_ms_min=k_ms[0], kernel_ms_median=k_ms[len(k_ms) // 2],
                 algorithmic_bytes=bytes_alg, flop=w.flop)

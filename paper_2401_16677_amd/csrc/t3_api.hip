@@ -162,13 +162,29 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   if (q.lag > p->tp) q.lag = p->tp;
   q.rows_per_agent = q.agents ? (int32_t)ceil_div(p->M, q.agents) : 0;
   if ((T + (int64_t)q.agents * (p->tp - 1)) >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
-  // start-up phase offsets (experiment knobs: T3_STAGGER="groups,window_ns")
+  // Start-up phase offsets (see stagger_start): four groups over a 12 us window, or half an
+  // estimated tile time if that is shorter, once there are tiles enough to fill the chip.
+  // The environment variable T3_STAGGER="groups,window_ns" overrides this ("0" turns it off).
   q.stagger_blocks = q.stagger_groups = q.stagger_ticks = 0;
-  if (const char *e = getenv("T3_STAGGER")) {
-    int g = 0, ns = 0;
-    if (sscanf(e, "%d,%d", &g, &ns) == 2 && g > 1 && ns > 0) {
+  {
+    int g = 4;
+    double window_ns = 12000.0;
+    const double tile_ns = 2.0 * *tm * *tn * (double)p->K / 6.25e3;   // at ~6.25 TFLOP/s per compute unit
+    if (window_ns > tile_ns / 2) window_ns = tile_ns / 2;
+    if (T < resident) g = 0;
+    if (const char *e = getenv("T3_STAGGER")) {
+      int eg = 0, ens = 0;
+      const int n = sscanf(e, "%d,%d", &eg, &ens);
+      if (n == 2 && eg > 1 && ens > 0) {
+        g = eg;
+        window_ns = ens;
+      } else if (n >= 1 && eg == 0) {
+        g = 0;
+      }
+    }
+    if (g > 1 && window_ns >= 100.0) {
       q.stagger_groups = g;
-      q.stagger_ticks = ns / 10 / g;          // 100 MHz ticks between consecutive groups
+      q.stagger_ticks = (int32_t)(window_ns / 10.0 / g);   // 100 MHz ticks between consecutive groups
       q.stagger_blocks = (int32_t)resident;
     }
   }
