@@ -83,6 +83,17 @@ typedef struct {
  *
  * Supported (tile_m, tile_n): (256,256), (256,128), (128,256), (128,128).
  *
+ * Size limits (T3_ERR_UNSUPPORTED beyond them): M*lda and N*ldb below 2^31 elements;
+ * M*ldr*4 and M*ldc*4 below 2^32 bytes (the kernels address R, C and a forward slot with
+ * 32-bit byte offsets from a uniform base); fewer than 2^31 tiles.
+ *
+ * Launch shape.  In the direct release mode and for t3_gemm the tile kernel runs persistent
+ * workgroups (as many as the device holds at once) that walk the grid positions in issue
+ * order.  The first wave of workgroups starts in a few phase groups a few microseconds
+ * apart, so that the compute units do not all reach their reduction traffic at the same
+ * moment; the environment variable T3_STAGGER="groups,window_ns" overrides the default
+ * (4 groups over 12 us), T3_STAGGER=0 turns it off.  Results do not depend on it.
+ *
  * Tracker state (Sec. 4.2): one caller-owned device array of t3_track_words(tp) uint32
  * words, cleared once by t3_track_reset().  It holds two banks of 3*tp + 2 words
  *   [0, tp)        counter[c]  tiles of chunk c that have landed

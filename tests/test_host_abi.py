@@ -95,6 +95,9 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert _fused_status(t3.problem(**ok, b_layout=t3.T3_B_KN)) == t3.T3_ERR_UNSUPPORTED
     assert _fused_status(t3.problem(**ok, flags=8)) == t3.T3_ERR_UNSUPPORTED
     assert _fused_status(t3.problem(**ok, b_layout=7)) == t3.T3_ERR_BAD_SHAPE
+    # R of 4 GiB or more (32-bit byte offsets in the kernels): refused, nothing launched
+    big = dict(M=65536, N=16384, K=64, tp=4, rank=0, tile_m=256, tile_n=256)
+    assert _fused_status(t3.problem(**big)) == t3.T3_ERR_UNSUPPORTED
     # empty problems are fine and launch nothing
     assert _fused_status(t3.problem(**{**ok, "M": 0})) == t3.T3_OK
     assert _fused_status(t3.problem(**{**ok, "N": 0})) == t3.T3_OK
