@@ -70,6 +70,9 @@ typedef struct {
                              tile_limit run (a deterministic prefix of the issue order; debugging
                              and tests)                                                              */
   uint32_t flags;         /* T3_FLAG_*                                                               */
+  int64_t tile_begin;     /* tiles whose issue index is below tile_begin do not run either: with
+                             tile_limit, [tile_begin, tile_limit) is a range of the issue order,
+                             e.g. one ring step s = [s*tpc, (s+1)*tpc) (Sec. 4.1).  0 = from the start  */
 } t3_problem;
 
 /*
@@ -109,7 +112,9 @@ typedef struct {
  * A launch of t3_gemm_rs_fused / t3_rs_reduce works in bank gen & 1; its last workgroup
  * clears the other bank and increments gen.  So consecutive launches need no reset in
  * between, and after a launch has completed its results are in bank (gen - 1) & 1.  A
- * launch that executes no tile (empty problem, tile_limit == 0) leaves the state untouched.
+ * launch that executes no tile (empty problem, empty tile range) leaves the state untouched.
+ * With a tile range, counters count the tiles of the range, and a chunk becomes ready (and
+ * is released) only if all of its tiles lie in the range.
  * Counter, ready and queue-as-a-set are deterministic; the order of queue entries follows
  * the order in which chunks actually completed on the device.  A tile's results are visible
  * to the whole device before it is counted, so a consumer that observes ready[c] (with an

@@ -138,21 +138,24 @@ def track(M, N, P, r, tile_m, tile_n, landed):
     return {"counter": counter, "ready": ready, "queue": queue, "queue_len": int(qlen.value)}
 
 
-def executed_mask(M, N, P, r, tile_m, tile_n, tile_limit):
-    """Boolean (M, N): element lies in one of the first tile_limit tiles of the issue order."""
+def executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin=0):
+    """Boolean (M, N): element lies in one of the tiles [tile_begin, tile_limit) of the issue
+    order; also returns the clipped range end and start."""
     W = N // P
     T = P * tiles_per_chunk(M, N, P, tile_m, tile_n)
     L = T if tile_limit < 0 else min(tile_limit, T)
+    B0 = min(max(tile_begin, 0), L)
     mask = np.zeros((M, N), dtype=bool)
-    for t in range(L):
+    for t in range(B0, L):
         _, c, mi, nj = tile_of(M, N, P, r, tile_m, tile_n, t)
         m0, n0 = mi * tile_m, c * W + nj * tile_n
         mask[m0:min(m0 + tile_m, M), n0:min(n0 + tile_n, (c + 1) * W)] = True
-    return mask, L
+    return mask, L, B0
 
 
 def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
-               tile_limit=-1, step0_store_only=False, fwd_direct=False, fwd_init=None):
+               tile_limit=-1, tile_begin=0, step0_store_only=False, fwd_direct=False,
+               fwd_init=None):
     """The whole path for one rank, by the definition.
 
     Returns a dict with
@@ -163,7 +166,9 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
     Default release mode: every executed tile is added in place into R and a chunk
     is copied to its forward slot once complete.  fwd_direct: sums of forwarded
     chunks go straight to the forward slot and R keeps the incoming data there.
-    Elements outside executed tiles keep their initial contents.
+    Only the tiles [tile_begin, tile_limit) of the issue order are executed (a ring step s is
+    the range [s*tpc, (s+1)*tpc), Sec. 4.1); elements outside executed tiles keep their
+    initial contents, and a chunk is complete only if all of its tiles were executed.
     """
     incoming = np.ascontiguousarray(incoming, dtype=np.float32)
     M, N = incoming.shape
@@ -173,8 +178,8 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
     order, own = chunk_order(P, r)
     C = gemm_rows(A_bits, B_bits, b_layout)
     S = reduce_rows(C, incoming, P, skip_chunk=int(order[0]) if step0_store_only else -1)
-    mask, L = executed_mask(M, N, P, r, tile_m, tile_n, tile_limit)
-    trk = track(M, N, P, r, tile_m, tile_n, np.arange(L, dtype=np.int64))
+    mask, L, B0 = executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin)
+    trk = track(M, N, P, r, tile_m, tile_n, np.arange(B0, L, dtype=np.int64))
 
     fwd = (np.zeros((max(P - 1, 0), M, W), dtype=np.float32) if fwd_init is None
            else np.array(fwd_init, dtype=np.float32, copy=True))
@@ -191,5 +196,5 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
                 fwd[s] = S[:, cols]
     out = dict(trk)
     out.update(R=R, fwd=fwd, owned=R[:, own * W:(own + 1) * W].copy(), order=order, own=own,
-               tiles_per_chunk=tiles_per_chunk(M, N, P, tile_m, tile_n), executed=L)
+               tiles_per_chunk=tiles_per_chunk(M, N, P, tile_m, tile_n), executed=L - B0)
     return out

@@ -124,6 +124,8 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.ldr = p->ldr;
   q.ldc = p->ldc;
   q.limit = (p->tile_limit < 0 || p->tile_limit > T) ? T : p->tile_limit;
+  q.begin = p->tile_begin < 0 ? 0 : (p->tile_begin > q.limit ? q.limit : p->tile_begin);
+  if (q.begin >= q.limit) *empty = true;       // an empty tile range: nothing to launch
   q.M = p->M;
   q.N = p->N;
   q.K = p->K;
@@ -190,8 +192,11 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   }
   // workgroups that will do work: the tiles below the limit and the release workgroups of the
   // forwarded chunks those tiles complete
-  const int64_t done_chunks = tpc > 0 ? q.limit / tpc : 0;
-  q.expected_done = (int32_t)(q.limit + q.agents * (done_chunks < p->tp - 1 ? done_chunks : p->tp - 1));
+  // chunks all of whose tiles lie in [begin, limit); the forwarded ones among them get released
+  int64_t released = 0;
+  for (int64_t s = 0; s + 1 < p->tp; ++s)
+    if (s * tpc >= q.begin && (s + 1) * tpc <= q.limit && tpc > 0) ++released;
+  q.expected_done = (int32_t)((q.limit - q.begin) + q.agents * released);
   q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
   q.resident = (int32_t)resident;
   return T3_OK;

@@ -59,6 +59,7 @@ struct Plan {
   uint32_t *track;
   int64_t lda, ldb, ldr, ldc;
   int64_t limit;     // tiles with issue index >= limit do nothing
+  int64_t begin;     // nor do tiles with issue index < begin
   int32_t M, N, K, P, rank, W, own;
   int32_t Mt, Wt, tpc;
   int32_t xcd_nbm, xcd_bmk, xcd_bnk;   // XCD grouping of a stage's tiles; xcd_nbm == 0: none
@@ -138,7 +139,7 @@ __device__ inline bool decode_tile(const Plan &p, int s, int j, Tile &tl) {
   tl.c = c;
   tl.mi = mi;
   tl.nj = nj;
-  return t < p.limit;
+  return t >= p.begin && t < p.limit;
 }
 
 // Grid layout: the tiles of stage 0, 1, ... in order; after the tiles of stage s come the
@@ -242,7 +243,8 @@ __device__ inline void track_count(const Plan &p, const Trk &t, int c) {
 // chunk was dispatched before this workgroup (lower block index), so the wait ends; should it
 // not (a broken launch), the workgroup gives up after kSpinLimit polls and raises the error word.
 __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_t *sh) {
-  if ((int64_t)(slot + 1) * p.tpc > p.limit) return;   // this chunk will not complete
+  if ((int64_t)(slot + 1) * p.tpc > p.limit || (int64_t)slot * p.tpc < p.begin)
+    return;                                              // this chunk will not complete
   const Trk t = trk_open(p);
   int c = p.rank + slot;
   if (c >= p.P) c -= p.P;

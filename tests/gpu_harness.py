@@ -13,7 +13,7 @@ def to_dev_bits(bits):
 
 
 def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfused=False,
-            ldr_pad=0, lda_pad=0):
+            ldr_pad=0, lda_pad=0, tile_begin=0):
     """One call of the fused path (or the unfused GEMM-then-reduce pair).  Returns a dict
     with R, fwd, counter, ready, queue, queue_len (numpy) and, for unfused, C."""
     M, K = a_bits.shape
@@ -36,7 +36,7 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
                      device=dev)
     track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
     p = t3.problem(M, N, K, tp, rank, tile[0], tile[1], lda=K + lda_pad, ldb=K + lda_pad,
-                   ldr=ldr, ldc=N, tile_limit=tile_limit, flags=flags)
+                   ldr=ldr, ldc=N, tile_limit=tile_limit, flags=flags, tile_begin=tile_begin)
     t3.t3_track_reset(tp, track)
     out = {}
     if unfused:

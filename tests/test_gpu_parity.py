@@ -111,6 +111,84 @@ def test_tile_limit_prefix_bit_exact(gpu, oracle, limit_kind, direct):
     _check_ints(got, want, tp, want["own"])
 
 
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("rng_kind", ["step1", "step_last", "straddle", "inside", "empty"])
+def test_tile_range_bit_exact(gpu, oracle, rng_kind, unfused, direct):
+    """[tile_begin, tile_limit): one ring step, ranges cutting through chunks, an empty range."""
+    M, N, K, tp, rank, tile = 300, 1536, 72, 3, 2, (128, 128)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=58)
+    tpc = oracle.tiles_per_chunk(M, N, tp, *tile)
+    begin, limit = {"step1": (tpc, 2 * tpc), "step_last": (2 * tpc, 3 * tpc),
+                    "straddle": (tpc - 2, 2 * tpc + 1), "inside": (tpc + 1, tpc + 3),
+                    "empty": (5, 5)}[rng_kind]
+    print(f"range=[{begin},{limit}) unfused={unfused} direct={direct}", flush=True)
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, tile_begin=begin, tile_limit=limit,
+                             fwd_direct=direct, fwd_init=sent)
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=_flags(False, direct), tile_begin=begin,
+                      tile_limit=limit, unfused=unfused)
+    assert np.array_equal(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"])
+    if rng_kind == "empty":
+        assert got["gen"] == 0          # nothing was launched
+    else:
+        _check_ints(got, want, tp, want["own"])
+
+
+@pytest.mark.parametrize("kind", ["integer", "normal"])
+def test_ring_of_virtual_ranks_closes_on_unsliced_gemm(gpu, oracle, kind):
+    """Whole ring reduce-scatter on one GPU (Sec. 2.3, Sec. 4.1): P virtual ranks, each with its own
+    K-slice, run ring step by ring step through the C ABI; after every step rank q's forward
+    slot is handed to rank q-1 as the incoming partial of its next chunk.  At the end every
+    rank must own the UNSLICED GEMM's columns of its chunk."""
+    import torch
+    P, M, W, ks, tile = 4, 512, 512, 192, (256, 256)
+    N, Kfull = P * W, P * ks
+    if kind == "integer":
+        a, b, _ = wl.make_integer_inputs(M, N, Kfull, seed=404)
+    else:
+        w = wl.make_shape("ring", M, N, Kfull, P, 0, *tile)
+        a, b, _ = wl.make_inputs(w, seed=405)
+    whole = oracle.gemm_rows(a, b)                       # fp64, all of K
+    dev = torch.device("cuda:0")
+    A_r = [gpu.to_dev_bits(np.ascontiguousarray(a[:, q * ks:(q + 1) * ks])) for q in range(P)]
+    B_r = [gpu.to_dev_bits(np.ascontiguousarray(b[:, q * ks:(q + 1) * ks])) for q in range(P)]
+    R_r = [torch.full((M, N), 99.0, dtype=torch.float32, device=dev) for _ in range(P)]
+    F_r = [torch.full((P - 1, M, W), gpu.SENTINEL, dtype=torch.float32, device=dev) for _ in range(P)]
+    T_r = [torch.zeros(t3.t3_track_words(P), dtype=torch.int32, device=dev) for _ in range(P)]
+    for q in range(P):
+        t3.t3_track_reset(P, T_r[q])
+    flags = t3.T3_FLAG_FWD_DIRECT | t3.T3_FLAG_STEP0_STORE_ONLY
+    tpc = oracle.tiles_per_chunk(M, N, P, *tile)
+    for s in range(P):
+        for q in range(P):
+            p = t3.problem(M, N, ks, P, q, *tile, flags=flags, tile_begin=s * tpc,
+                           tile_limit=(s + 1) * tpc)
+            t3.t3_gemm_rs_fused(p, A_r[q], B_r[q], R_r[q], F_r[q], T_r[q])
+        torch.cuda.synchronize()
+        for q in range(P):
+            tr = t3.read_track(T_r[q], P)
+            c = (q + s) % P
+            assert tr["gen"] == s + 1 and tr["error"] == 0
+            assert tr["counter"][c] == tpc and tr["ready"][c] == 1 and tr["counter"].sum() == tpc
+            assert tr["queue_len"] == (1 if s < P - 1 else 0)
+            if s < P - 1:                # the triggered chunk travels to the downstream neighbour
+                assert tr["queue"][0] == c
+                R_r[(q - 1) % P][:, c * W:(c + 1) * W] = F_r[q][s]
+    print(f"ring of {P} ranks, {kind} inputs", flush=True)
+    for q in range(P):
+        own = (q - 1) % P
+        got = R_r[q][:, own * W:(own + 1) * W].cpu().numpy()
+        want = whole[:, own * W:(own + 1) * W]
+        if kind == "integer":
+            assert np.array_equal(got, want.astype(np.float32))
+        else:
+            e = gpu.rel_err(got, want)
+            print(f"rank {q} owns chunk {own}: normwise error {e:.2e}", flush=True)
+            assert e <= EXPECT
+
+
 def test_tiny_outproj_config_float_parity(gpu, oracle):
     w = wl.WORKLOADS["tiny_outproj"]
     a, b, inc = wl.make_inputs(w)

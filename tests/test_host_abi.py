@@ -25,9 +25,10 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_problem_struct_matches_header_layout():
-    # 8 int32, 5 int64, 1 uint32 (+ padding to 8)
-    assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8
+    # 8 int32, 5 int64, 1 uint32 (+ padding to 8), 1 int64
+    assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8 + 8
     assert t3.T3Problem.lda.offset == 32 and t3.T3Problem.flags.offset == 72
+    assert t3.T3Problem.tile_begin.offset == 80
 
 
 @pytest.mark.parametrize("tp", [1, 2, 4, 8, 16])

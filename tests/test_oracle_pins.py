@@ -212,6 +212,51 @@ def test_emulated_ring_closes_on_unsliced_gemm(oracle, P):
         assert np.array_equal(out[r]["owned"], whole[:, own * W:(own + 1) * W].astype(np.float32))
 
 
+@pytest.mark.parametrize("P", [3, 4])
+def test_ring_steps_as_tile_ranges_compose_to_the_whole_path(oracle, P):
+    """One ring step is the range [s*tpc, (s+1)*tpc) of the issue order (Sec. 4.1).  Running the
+    steps one by one, each on what the previous left, must give what one full run gives; and
+    the step-by-step ring of P ranks (first chunk stored, not added) closes on the unsliced GEMM."""
+    M, W, ks, tm, tn = 8, 6, 16, 4, 3
+    N, Kfull = P * W, P * ks
+    a, b, inc0 = wl.make_integer_inputs(M, N, Kfull, seed=77 + P)
+    tpc = oracle.tiles_per_chunk(M, N, P, tm, tn)
+    # (1) composition on one rank, in-place release mode
+    r = 1
+    A1, B1 = np.ascontiguousarray(a[:, :ks]), np.ascontiguousarray(b[:, :ks])
+    full = oracle.fused_path(A1, B1, inc0, P, r, tm, tn)
+    R, fwd = inc0.copy(), np.zeros((P - 1, M, W), np.float32)
+    ready = np.zeros(P, np.uint32)
+    for s in range(P):
+        out = oracle.fused_path(A1, B1, R, P, r, tm, tn, tile_begin=s * tpc,
+                                tile_limit=(s + 1) * tpc, fwd_init=fwd)
+        assert out["executed"] == tpc and out["ready"].sum() == 1
+        assert out["queue_len"] == (1 if s < P - 1 else 0)
+        R, fwd, ready = out["R"], out["fwd"], ready + out["ready"]
+    assert np.array_equal(R, full["R"]) and np.array_equal(fwd, full["fwd"])
+    assert np.all(ready == 1)
+    # (2) the ring, step by step over all ranks
+    whole = (wl.bf16_bits_to_f32(a).astype(np.int64) @ wl.bf16_bits_to_f32(b).astype(np.int64).T)
+    A_r = [np.ascontiguousarray(a[:, q * ks:(q + 1) * ks]) for q in range(P)]
+    B_r = [np.ascontiguousarray(b[:, q * ks:(q + 1) * ks]) for q in range(P)]
+    Rr = [np.full((M, N), 99.0, np.float32) for _ in range(P)]      # garbage: step 0 must not read it
+    Fr = [np.zeros((P - 1, M, W), np.float32) for _ in range(P)]
+    for s in range(P):
+        outs = [oracle.fused_path(A_r[q], B_r[q], Rr[q], P, q, tm, tn, tile_begin=s * tpc,
+                                  tile_limit=(s + 1) * tpc, step0_store_only=True,
+                                  fwd_direct=True, fwd_init=Fr[q]) for q in range(P)]
+        for q in range(P):
+            Rr[q], Fr[q] = outs[q]["R"], outs[q]["fwd"]
+        if s < P - 1:
+            for q in range(P):           # rank q's slot s is what rank q-1 receives for its step s+1
+                c = int(outs[q]["order"][s])
+                Rr[(q - 1) % P][:, c * W:(c + 1) * W] = Fr[q][s]
+    for q in range(P):
+        own = (q - 1) % P
+        assert np.array_equal(Rr[q][:, own * W:(own + 1) * W],
+                              whole[:, own * W:(own + 1) * W].astype(np.float32))
+
+
 # ---------------------------------------------------------------- tiles, tracker, prefixes
 
 @pytest.mark.parametrize("M,N,P,r,tm,tn", [(8, 12, 3, 1, 4, 2), (10, 12, 2, 0, 4, 4),
@@ -277,7 +322,7 @@ def test_prefix_leaves_unexecuted_tiles_untouched(oracle, direct):
     L = tpc + 2
     part = oracle.fused_path(a, b, inc, P, r, tm, tn, tile_limit=L, fwd_direct=direct,
                              fwd_init=sentinel)
-    mask, nexec = oracle.executed_mask(M, N, P, r, tm, tn, L)
+    mask, nexec, _ = oracle.executed_mask(M, N, P, r, tm, tn, L)
     assert nexec == L and mask.sum() == sum(
         (min(tm, M - mi * tm)) * tn for mi in [oracle.tile_of(M, N, P, r, tm, tn, t)[2]
                                                for t in range(L)])
