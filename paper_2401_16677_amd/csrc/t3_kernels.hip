@@ -21,6 +21,9 @@
 #ifndef T3_MH
 #define T3_MH 2
 #endif
+#ifndef T3_STREAM
+#define T3_STREAM 0   // 1: two-stage fused kernels stream the incoming partial in during the main loop
+#endif
 #ifndef T3_AGENTS
 #define T3_AGENTS 32          // release workgroups per forwarded chunk (multiple of 8)
 #endif
@@ -90,7 +93,9 @@ __device__ inline Trk trk_open(const Plan &p) {
   Trk t;
   t.gen = p.track + 2 * trk_bank_words(p.P);
   t.error = t.gen + 1;
-  const uint32_t g = __hip_atomic_load(t.gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // (the same in every lane: made uniform so that the bank pointers live in scalar registers)
+  const uint32_t g = __builtin_amdgcn_readfirstlane(
+      __hip_atomic_load(t.gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
   uint32_t *b = p.track + (g & 1u) * trk_bank_words(p.P);
   t.counter = b;
   t.ready = b + p.P;
@@ -347,7 +352,7 @@ void gemm_tile_kernel(const Plan p) {
   constexpr int NA = BM / kRPC / NW, NB = BN / kRPC / NW;   // copies per wavefront per slab
   constexpr int NL = NA + NB;
   constexpr int NBLK = FM * FN;
-  constexpr bool STREAM = (MODE == kModeFused) && NSTAGE == 2;
+  constexpr bool STREAM = T3_STREAM && (MODE == kModeFused) && NSTAGE == 2;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int kBOff = BM * kRowBytes;
   constexpr int kRingBytes = STREAM ? NW * kRingSlots * 1024 : 0;
@@ -472,31 +477,6 @@ void gemm_tile_kernel(const Plan p) {
   const int rw0 = m0 + wm * WM, cw0 = n0 + wn * WN;          // wavefront tile origin (uniform)
   const bool full = (rw0 + WM <= p.M) && (cw0 + WN <= col_hi);
   const int lrow = rw0 + fr, lcol = cw0 + 4 * fq;            // this lane's row / first column, block (0,0)
-  // Streaming kernels take the incoming partial in during the main loop, two blocks (a "pair")
-  // at a time, if K is long enough for all NBLK / 2 pairs; otherwise it is loaded here.
-  constexpr int NPAIR = NBLK / 2;
-  static_assert(FN % 2 == 0, "pairs");
-  const bool streaming = STREAM && !store_only && nkf >= NPAIR + 2;
-  const int n_pre = streaming ? 0 : NBLK;
-  // Every access to R, C or a forward slot is (uniform base) + (32-bit byte offset of the lane),
-  // the offset formed per block when it is needed: byte sizes of these arrays stay below 4 GiB.
-  f32x4 acc[FM][FN];
-  {
-    const uint32_t ld_in = (uint32_t)p.ldr;
-    const __amdgpu_buffer_rsrc_t in_rsrc = make_rsrc(p.R, (uint32_t)p.M * ld_in * 4u);
-    const uint32_t in_lane = ((uint32_t)lrow * ld_in + (uint32_t)lcol) * 4u;
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (MODE == kModeFused && !store_only && i * FN + j < n_pre)
-          if (full || (lrow + 16 * i < p.M && lcol + 16 * j < col_hi))
-            v = load_stream(in_rsrc, in_lane, ((uint32_t)(16 * i) * ld_in + (uint32_t)(16 * j)) * 4u);
-        acc[i][j] = v;
-      }
-  }
-
   // ---- "pairs".  Global accesses that touch half a 128-byte line per row (what one 16 x 16
   // block in the accumulator layout amounts to) run at a third of the rate of full lines, so
   // the incoming partial and the results move in units of one PAIR = two neighbouring blocks =
@@ -524,6 +504,51 @@ void gemm_tile_kernel(const Plan p) {
   };
   const PairLane ul = pair_lane(lane);           // (streaming kernels only: the epilogue recomputes it)
   const int *u_row = ul.row, *u_col = ul.col, *u_acc = ul.acc;
+
+  // Streaming kernels take the incoming partial in during the main loop, two blocks (a "pair")
+  // at a time, if K is long enough for all NBLK / 2 pairs; otherwise it is loaded here.
+  constexpr int NPAIR = NBLK / 2;
+  static_assert(FN % 2 == 0, "pairs");
+  const bool streaming = STREAM && !store_only && nkf >= NPAIR + 2;
+  const int n_pre = streaming ? 0 : NBLK;
+  // Every access to R, C or a forward slot is (uniform base) + (32-bit byte offset of the lane),
+  // the offset formed per block when it is needed: byte sizes of these arrays stay below 4 GiB.
+  f32x4 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (MODE == kModeFused && !store_only && n_pre) {
+    // The incoming partial, loaded before the main loop: every pair as two full-line accesses
+    // (8 rows x 128 bytes), all in flight together, landing in the pair's accumulator registers;
+    // then pair by pair through LDS into the accumulator layout.  The scratch is the last
+    // stage, which no copy touches before the main loop's first barrier.
+    const uint32_t ld_in = (uint32_t)p.ldr;
+    const __amdgpu_buffer_rsrc_t in_rsrc = make_rsrc(p.R, (uint32_t)p.M * ld_in * 4u);
+    uint32_t in_l[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      in_l[h] = ((uint32_t)(rw0 + u_row[h]) * ld_in + (uint32_t)(cw0 + u_col[h])) * 4u;
+#pragma unroll
+    for (int t = 0; t < NPAIR; ++t) {
+      const int i = t / UJ, jj = t % UJ;
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
+          acc[i][2 * jj + h] = load_stream(in_rsrc, in_l[h], ((uint32_t)(16 * i) * ld_in + (uint32_t)(32 * jj)) * 4u);
+    }
+    char *scr = lds + (NSTAGE - 1) * kStageBytes + wave * (kRingSlots * 1024);
+#pragma unroll
+    for (int t = 0; t < NPAIR; ++t) {
+      const int i = t / UJ, jj = t % UJ;
+      char *slot = scr + ((2 * t) & (kRingSlots - 1)) * 1024;
+      *(f32x4 *)(slot + lane * 16) = acc[i][2 * jj];
+      *(f32x4 *)(slot + 1024 + lane * 16) = acc[i][2 * jj + 1];
+      acc[i][2 * jj] = *(const f32x4 *)(slot + u_acc[0]);
+      acc[i][2 * jj + 1] = *(const f32x4 *)(slot + u_acc[1]);
+      if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+  }
 
   // ---- the incoming-partial ring (streaming kernels): four slots per wavefront, pair t in
   // slots {0, 1} (t even) or {2, 3} (t odd).
