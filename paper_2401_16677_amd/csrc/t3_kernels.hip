@@ -21,9 +21,6 @@
 #ifndef T3_MH
 #define T3_MH 2
 #endif
-#ifndef T3_STREAM
-#define T3_STREAM 0   // 1: two-stage fused kernels stream the incoming partial in during the main loop
-#endif
 #ifndef T3_AGENTS
 #define T3_AGENTS 32          // release workgroups per forwarded chunk (multiple of 8)
 #endif
@@ -323,7 +320,7 @@ __device__ inline void sched_kstep() {
   }
 }
 
-constexpr int kRingSlots = 4;         // 1-KiB slots per wavefront of the incoming-partial ring
+constexpr int kRingSlots = 4;         // 1-KiB LDS slots per wavefront for transposing pairs: two pairs
 
 // WAVES_M x WAVES_N wavefronts per workgroup, each producing a (BM/WAVES_M) x (BN/WAVES_N)
 // block of the tile out of 16 x 16 MFMA blocks; NSTAGE LDS stages, NSTAGE-1 slabs in flight.
@@ -331,14 +328,6 @@ constexpr int kRingSlots = 4;         // 1-KiB slots per wavefront of the incomi
 // The products are formed transposed (the B rows go in as the MFMA's first operand, the A rows
 // as its second), so that a lane ends up holding, per block, one output row and FOUR
 // CONSECUTIVE COLUMNS: the incoming partial is read and the sum written with 16-byte accesses.
-//
-// Fused kernels with two stages stream the incoming partial in DURING the main loop (a compute
-// unit pulls data that is not in its L2 at only ~11 bytes/clock, so fetching a tile's 256 KiB
-// up front would idle the matrix cores for a third of the tile's time): each iteration a
-// wavefront copies one or two of its own 16 x 16 blocks global -> LDS into a private ring of
-// four 1-KiB slots, in the accumulator layout, behind the slab copies in issue order; two
-// iterations later the block has landed (it is older than the slab copies the next wait is
-// for), is read back and added to its accumulators.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2)))
 void gemm_tile_kernel(const Plan p) {
@@ -352,18 +341,16 @@ void gemm_tile_kernel(const Plan p) {
   constexpr int NA = BM / kRPC / NW, NB = BN / kRPC / NW;   // copies per wavefront per slab
   constexpr int NL = NA + NB;
   constexpr int NBLK = FM * FN;
-  constexpr bool STREAM = T3_STREAM && (MODE == kModeFused) && NSTAGE == 2;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int kBOff = BM * kRowBytes;
-  constexpr int kRingBytes = STREAM ? NW * kRingSlots * 1024 : 0;
   static_assert(NA * kRPC * NW == BM && NB * kRPC * NW == BN, "copies must tile the slab");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * NL < 64, "vmcnt range");
   static_assert(KS == 2, "the loop body is written as two k-steps");
   static_assert(NL % MH == 0, "a slab's copies are split evenly over the first k-step's passes");
   static_assert((FN & (FN - 1)) == 0, "block index -> (row block, column block) by shifts");
-  static_assert(NSTAGE * kStageBytes + kRingBytes <= 160 * 1024, "LDS");
+  static_assert(NSTAGE * kStageBytes <= 160 * 1024, "LDS");
 
-  __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes + kRingBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes];
 
   // Persistent workgroups: workgroup w takes grid positions w, w + gridDim.x, ... in order (a
   // position is a tile or a piece of release work).  The tracking of a finished tile is
@@ -502,15 +489,11 @@ void gemm_tile_kernel(const Plan p) {
     u.acc[1] = h * 1024 + rq * 128 + ((4 + q) ^ r) * 16;
     return u;
   };
-  const PairLane ul = pair_lane(lane);           // (streaming kernels only: the epilogue recomputes it)
+  const PairLane ul = pair_lane(lane);           // (for the loads just below; the epilogue recomputes it)
   const int *u_row = ul.row, *u_col = ul.col, *u_acc = ul.acc;
 
-  // Streaming kernels take the incoming partial in during the main loop, two blocks (a "pair")
-  // at a time, if K is long enough for all NBLK / 2 pairs; otherwise it is loaded here.
   constexpr int NPAIR = NBLK / 2;
   static_assert(FN % 2 == 0, "pairs");
-  const bool streaming = STREAM && !store_only && nkf >= NPAIR + 2;
-  const int n_pre = streaming ? 0 : NBLK;
   // Every access to R, C or a forward slot is (uniform base) + (32-bit byte offset of the lane),
   // the offset formed per block when it is needed: byte sizes of these arrays stay below 4 GiB.
   f32x4 acc[FM][FN];
@@ -518,7 +501,7 @@ void gemm_tile_kernel(const Plan p) {
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (MODE == kModeFused && !store_only && n_pre) {
+  if (MODE == kModeFused && !store_only) {
     // The incoming partial, loaded before the main loop: every pair as two full-line accesses
     // (8 rows x 128 bytes), all in flight together, landing in the pair's accumulator registers;
     // then pair by pair through LDS into the accumulator layout.  The scratch is the last
@@ -549,43 +532,6 @@ void gemm_tile_kernel(const Plan p) {
       if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
   }
-
-  // ---- the incoming-partial ring (streaming kernels): four slots per wavefront, pair t in
-  // slots {0, 1} (t even) or {2, 3} (t odd).
-  char *ring = lds + NSTAGE * kStageBytes + wave * (kRingSlots * 1024);
-  int c1 = 0;                                    // incoming copies issued in the previous iteration
-  uint32_t in_u[2];                              // byte offsets of the linear side in R, rows of ldr
-#pragma unroll
-  for (int h = 0; h < 2; ++h) in_u[h] = ((uint32_t)u_row[h] * (uint32_t)p.ldr + (uint32_t)u_col[h]) * 4u;
-  auto issue_pair = [&](int t) {                 // the two copies of pair t
-    const int i = t / UJ, jj = t % UJ;
-    const int pr = rw0 + 16 * i, pc = cw0 + 32 * jj;          // pair origin (uniform)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t dst = lds_base + NSTAGE * kStageBytes + wave * (kRingSlots * 1024) +
-                           (((2 * t) & (kRingSlots - 1)) + h) * 1024;
-      const char *base = (const char *)p.R;
-      uint32_t off;
-      if (full) {
-        base += ((int64_t)pr * p.ldr + pc) * 4;
-        off = in_u[h];
-      } else {  // rows and columns past the ragged edge are clamped: what lands there is never stored
-        const int rr = min(pr + u_row[h], p.M - 1), cc = min(pc + u_col[h], col_hi - 4);
-        off = ((uint32_t)rr * (uint32_t)p.ldr + (uint32_t)cc) * 4u;
-      }
-      // the slot's previous pair has been read back (lgkmcnt) before it is overwritten
-      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :
-                   : "s"(dst), "v"(off), "s"(base)
-                   : "memory");
-    }
-  };
-  auto add_pair = [&](int t) {                   // t is a constant wherever this is called
-    const int i = t / UJ, jj = t % UJ;
-    const char *slot = ring + ((2 * t) & (kRingSlots - 1)) * 1024;
-    acc[i][2 * jj] += *(const f32x4 *)(slot + u_acc[0]);
-    acc[i][2 * jj + 1] += *(const f32x4 *)(slot + u_acc[1]);
-  };
 
   if (nkf > 0) {
 #pragma unroll
@@ -620,46 +566,29 @@ void gemm_tile_kernel(const Plan p) {
   // ---- main loop: slab kt is multiplied while the next NSTAGE-1 slabs are in flight.  The
   // products of a slab's last micro-step are issued after the next barrier, under the next
   // slab's first LDS reads.  An iteration is: wait + barrier; k-step 0, with the next slab's
-  // copies spread over its row passes; the incoming-partial work, if any; k-step 1.
-  //
-  // Streaming schedule (pairs must be named by constants to stay in registers, so the loop is
-  // laid out as NPAIR phases, one copy of the loop body per phase): iteration 0 issues pair 0;
-  // phase t = 1 .. NPAIR-1 runs up to iteration t (nkf-2) / NPAIR, in which it adds pair t-2 and
-  // issues pair t; the first two iterations after the phases add the last two pairs; what the
-  // loop did not get to is added after it.  A pair is added two or more iterations after it
-  // was issued: by then it has landed, being older than slab copies already waited for.
+  // copies spread over its row passes; k-step 1.
   constexpr int kWaitSlab = wait_vm((NSTAGE - 2) * NL);
   if (nkf > 0) {
-    __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the blocks loaded up front) landed
+    __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the incoming partial) landed
     __builtin_amdgcn_s_barrier();
     if (MODE == kModeFused && pending_c >= 0) {    // (also older: the previous tile's stores)
       track_count(p, trk, pending_c);
       pending_c = -1;
     }
     issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
-    if (STREAM && streaming) {
-      issue_pair(0);
-      c1 = 2;
-    }
     read_u(0, 0);
 #pragma unroll
     for (int u = 1; u < US; ++u) {
       read_u(u, 0);
       mfma_u(u - 1);
     }
-    int stage = 1, kt = 1;
-    auto iteration = [&](auto &&stream_ops) {      // one slab; stream_ops() returns copies issued
+    int stage = 1;
+    for (int kt = 1; kt < nkf; ++kt) {
       const int so = stage * kStageBytes;
       const int kt_next = min(kt + NSTAGE - 1, nkf - 1);
       const int st_next = stage >= 1 ? stage - 1 : NSTAGE - 1;
       asm volatile("" ::: "memory");               // LDS reads above stay above the barrier
-      // own copies of slab kt landed (the c1 younger incoming copies may still fly), own LDS reads done
-      if (STREAM) {
-        if (c1) __builtin_amdgcn_s_waitcnt(wait_vm(2) & kWaitLgkm0);
-        else __builtin_amdgcn_s_waitcnt(wait_vm(0) & kWaitLgkm0);
-      } else {
-        __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);
-      }
+      __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);   // own copies of slab kt landed, own LDS reads done
       __builtin_amdgcn_s_barrier();                // everyone's; all are done with the stage refilled next
 #pragma unroll
       for (int u = 0; u < MH; ++u) {               // k-step 0
@@ -668,7 +597,6 @@ void gemm_tile_kernel(const Plan p) {
         mfma_u((u + US - 1) % US);                 // u == 0: last micro-step of slab kt-1
       }
       sched_kstep<MH, FMH, FN, 0>();
-      if (STREAM) c1 = stream_ops();
 #pragma unroll
       for (int u = MH; u < US; ++u) {              // k-step 1
         read_u(u, so);
@@ -676,41 +604,9 @@ void gemm_tile_kernel(const Plan p) {
       }
       sched_kstep<MH, FMH, FN, 0>();
       stage = stage == NSTAGE - 1 ? 0 : stage + 1;
-      ++kt;
-    };
-    int pairs_added = 0, pairs_issued = (STREAM && streaming) ? 1 : 0;
-    if (STREAM && streaming) {
-#pragma unroll
-      for (int t = 1; t < NPAIR; ++t) {
-        const int at = (t * (nkf - 2)) / NPAIR;    // pair t is issued in iteration at: evenly spread
-        bool mine;
-        do {
-          mine = (kt == at);
-          iteration([&]() {
-            if (!mine) return 0;
-            if (t >= 2) add_pair(t - 2);
-            issue_pair(t);
-            return 2;
-          });
-        } while (!mine);
-      }
-      pairs_added = NPAIR - 2;
-      pairs_issued = NPAIR;
     }
-    for (int r = (STREAM && streaming) ? 0 : 2; kt < nkf; ++r)
-      iteration([&]() {
-        if (r == 0) add_pair(NPAIR - 2);
-        if (r == 1) add_pair(NPAIR - 1);
-        if (r < 2) ++pairs_added;
-        return 0;
-      });
     mfma_u(US - 1);
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies and the last pairs
-    if (STREAM) {
-#pragma unroll
-      for (int t = 0; t < NPAIR; ++t)
-        if (t >= pairs_added && t < pairs_issued) add_pair(t);
-    }
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies
   }
   asm volatile("" ::: "memory");
 
