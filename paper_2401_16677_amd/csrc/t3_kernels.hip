@@ -1,16 +1,15 @@
 // Device code of the fused sliced-GEMM + reduce-scatter-reduction path for gfx950 (CDNA4).
 //
-// One workgroup (256 threads = 4 wavefronts of 64, arranged 2 x 2) produces one BM x BN
-// output tile with v_mfma_f32_32x32x16_bf16.  K-slabs of 32 bf16 of A and B are copied
-// global -> LDS without passing through registers (global_load_lds_dwordx4) into a ring of
-// three stages, two slabs ahead of the one being multiplied; LDS rows are XOR-swizzled so
-// that the MFMA operand reads are bank-conflict free.  Two workgroups fit on a compute unit:
-// while one waits on memory (its incoming partial, its stores) the other keeps the matrix
-// cores busy.
+// A persistent workgroup of 8 wavefronts (4 for the smallest tile) produces BM x BN output
+// tiles with v_mfma_f32_16x16x32_bf16.  K-slabs of 64 bf16 of A and B are copied global -> LDS
+// without passing through registers (global_load_lds_dwordx4) into two or three stages, ahead
+// of the slab being multiplied; LDS rows are XOR-swizzled so that the MFMA operand reads are
+// bank-conflict free.
 //
 // The reduction of Sec. 4.3 of the T3 paper (op-and-store into the buffer that also receives
 // the upstream partial) is done by starting the accumulators from the incoming partial, so a
-// tile is read once at its start and written once at its end.
+// tile is read once at its start and written once at its end; both moves use full 128-byte
+// lines and are transposed to and from the accumulator layout through LDS.
 //
 // Included by t3_api.hip only.
 #pragma once
@@ -19,7 +18,7 @@
 #include <stdint.h>
 
 #ifndef T3_MH
-#define T3_MH 2
+#define T3_MH 2            // row passes per MFMA k-step of a 128-row wavefront tile (2 or 4)
 #endif
 #ifndef T3_AGENTS
 #define T3_AGENTS 32          // release workgroups per forwarded chunk (multiple of 8)

@@ -49,8 +49,7 @@ EXACT_CASES = [
     (100, 64, 8, 8, 5, (128, 128)),
     (600, 1280, 104, 2, 0, (256, 256)),
     (512, 2048, 160, 4, 3, (256, 256)),
-    # K long enough for the incoming partial to be streamed in during the main loop (at least
-    # 18 slabs of 64 for the 256 x 256 tile, 10 for the 128 x 128 tile), full and ragged tiles
+    # long K (11 to 64 slabs of 64), full and ragged tiles
     (512, 1024, 1216, 2, 1, (256, 256)),
     (600, 1280, 1160, 2, 0, (256, 256)),
     (300, 800, 712, 4, 2, (128, 128)),
