@@ -57,6 +57,15 @@ typedef enum {
                                        direct reduce-scatter of Sec. 7.1); R keeps the incoming
                                        data there                                                    */
 
+#define T3_FLAG_TWO_WRITERS 4u      /* the rank's buffer R receives TWO updates per element, as in the
+                                       paper's ring reduce-scatter (Sec. 4.1, Sec. 4.2.1): the local
+                                       GEMM's tile (t3_gemm_rs_fused) and the upstream neighbour's
+                                       update (t3_upstream_update), each an atomic add (the
+                                       op-and-store of Sec. 4.3) into R, in either order or at the
+                                       same time; a chunk is ready after both.  With
+                                       T3_FLAG_STEP0_STORE_ONLY chunk order[0] has no upstream update.
+                                       Not combinable with T3_FLAG_FWD_DIRECT.                        */
+
 typedef struct {
   int32_t M, N, K;        /* tokens, hidden size, slice width of this rank                           */
   int32_t tp, rank;       /* ring size and this rank's position                                      */
@@ -174,6 +183,31 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
    written to R / fwd, and drives the same tracker, tile by tile in the same order. */
 t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd,
                        uint32_t *track, void *stream);
+
+/*
+ * Two-writer mode (T3_FLAG_TWO_WRITERS in p->flags for all three calls below).
+ *
+ *   R     fp32 [M][ldr]   in: what has been accumulated so far (zero before the first update of
+ *                         a reduction).  out: + C on the tiles t3_gemm_rs_fused ran, + incoming
+ *                         on the tiles t3_upstream_update ran.
+ *
+ * t3_gemm_rs_fused adds its tiles into R and counts them; it releases nothing (fwd is ignored and
+ * may be NULL).  t3_upstream_update stands in for the upstream neighbour's DMA updates: it adds
+ * `incoming` (fp32 [M][ldc]) into R tile by tile in the same issue order and counts every tile in
+ * the same tracker; with T3_FLAG_STEP0_STORE_ONLY it skips chunk order[0].  The two calls must
+ * use the same problem (tile range included) and tracker state and may run on different streams
+ * at the same time; both must be enqueued after whatever used the tracker before has completed,
+ * and BOTH must be made: the tracker closes its bank when the tiles of both have been counted.
+ * A chunk's threshold is 2 * tpc (tpc for chunk order[0] under T3_FLAG_STEP0_STORE_ONLY).
+ *
+ * t3_release_chunks is the triggered transfer (Sec. 4.2.2) as a call of its own: ordered after
+ * both updates, it copies every forwarded chunk whose ready flag the last completed launch left
+ * set from R into its forward slot.  It changes no tracker state.
+ */
+t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *R,
+                             uint32_t *track, void *stream);
+t3_status t3_release_chunks(const t3_problem *p, const float *R, float *fwd,
+                            const uint32_t *track, void *stream);
 
 const char *t3_status_string(t3_status s);
 

@@ -17,7 +17,9 @@
  *     chunks are forwarded later, last chunk stays" map (Sec. 4.1, Sec. 4.4);
  *   - tracker: count updates per tracked region against a threshold, the write
  *     that reaches the threshold triggers the transfer; a per-transfer counter
- *     when a transfer block spans several tracked regions (Sec. 4.2.1, 4.2.2).
+ *     when a transfer block spans several tracked regions (Sec. 4.2.1, 4.2.2);
+ *     the threshold scales with the updates expected per element, 2 where the
+ *     upstream neighbour's update lands in the same memory (Sec. 4.2.1).
  *
  * Numerics: bf16 inputs are widened exactly, products are exact in fp64, sums
  * are accumulated in fp64 in ascending k, and the reduced value is rounded to
@@ -193,18 +195,22 @@ int t3o_tile_of(int32_t M, int32_t N, int32_t P, int32_t r,
 
 /*
  * Track & trigger replay (Sec. 4.2.1, Sec. 4.2.2), at chunk granularity: each
- * landed tile increments the counter of the chunk it belongs to; the landing
- * that brings a counter to the threshold (tiles per chunk) marks the chunk
- * ready and, unless it is the chunk the rank keeps, appends it to the trigger
- * queue.  `landed` lists tile issue indices in the order their writes land.
- * counter/ready/queue have P entries; queue is filled in trigger order and
- * unused entries are left at 0xFFFFFFFF.
+ * landed tile update increments the counter of the chunk it belongs to; the
+ * landing that brings a counter to the threshold marks the chunk ready and,
+ * unless it is the chunk the rank keeps, appends it to the trigger queue.
+ * The threshold is (tiles per chunk) x (updates expected per element of the
+ * chunk): 1 where only the local GEMM writes, 2 where the upstream
+ * neighbour's update lands in the same memory as well, which is the ring
+ * reduce-scatter case of Sec. 4.2.1.  updates == NULL means 1 everywhere.
+ * `landed` lists tile issue indices in the order their writes land (a tile
+ * appears once per writer).  counter/ready/queue have P entries; queue is
+ * filled in trigger order and unused entries are left at 0xFFFFFFFF.
  */
-int t3o_track(int32_t M, int32_t N, int32_t P, int32_t r,
-              int32_t tile_m, int32_t tile_n,
-              const int64_t *landed, int64_t nlanded,
-              uint32_t *counter, uint32_t *ready, uint32_t *queue,
-              uint32_t *queue_len)
+int t3o_track_upd(int32_t M, int32_t N, int32_t P, int32_t r,
+                  int32_t tile_m, int32_t tile_n, const int32_t *updates,
+                  const int64_t *landed, int64_t nlanded,
+                  uint32_t *counter, uint32_t *ready, uint32_t *queue,
+                  uint32_t *queue_len)
 {
     if (M <= 0 || N <= 0 || P <= 0 || r < 0 || r >= P || N % P != 0 ||
         tile_m <= 0 || tile_n <= 0 || nlanded < 0 || (nlanded && !landed) ||
@@ -214,6 +220,8 @@ int t3o_track(int32_t M, int32_t N, int32_t P, int32_t r,
     const int64_t tpc = (int64_t)((M + tile_m - 1) / tile_m) * ((W + tile_n - 1) / tile_n);
     const int32_t own = (r + P - 1) % P;
     for (int32_t c = 0; c < P; ++c) {
+        if (updates && updates[c] < 1)
+            return T3O_BAD_ARG;
         counter[c] = 0;
         ready[c] = 0;
         queue[c] = 0xFFFFFFFFu;
@@ -225,7 +233,7 @@ int t3o_track(int32_t M, int32_t N, int32_t P, int32_t r,
             return T3O_BAD_ARG;
         const int32_t c = (int32_t)((r + t / tpc) % P);
         counter[c] += 1;
-        if ((int64_t)counter[c] == tpc) {
+        if ((int64_t)counter[c] == tpc * (updates ? updates[c] : 1)) {
             ready[c] = 1;
             if (c != own) {
                 queue[*queue_len] = (uint32_t)c;
@@ -234,4 +242,14 @@ int t3o_track(int32_t M, int32_t N, int32_t P, int32_t r,
         }
     }
     return T3O_OK;
+}
+
+int t3o_track(int32_t M, int32_t N, int32_t P, int32_t r,
+              int32_t tile_m, int32_t tile_n,
+              const int64_t *landed, int64_t nlanded,
+              uint32_t *counter, uint32_t *ready, uint32_t *queue,
+              uint32_t *queue_len)
+{
+    return t3o_track_upd(M, N, P, r, tile_m, tile_n, NULL, landed, nlanded, counter, ready,
+                         queue, queue_len);
 }

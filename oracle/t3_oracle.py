@@ -47,6 +47,8 @@ def lib():
                                   _p, _p, _p, _p]
         L.t3o_track.argtypes = [_c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _p, _c_i64,
                                 _p, _p, _p, _p]
+        L.t3o_track_upd.argtypes = [_c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _c_i32, _p, _p,
+                                    _c_i64, _p, _p, _p, _p]
         _lib = L
     return _lib
 
@@ -126,15 +128,19 @@ def tiles_per_chunk(M, N, P, tile_m, tile_n):
     return -(-M // tile_m) * -(-W // tile_n)
 
 
-def track(M, N, P, r, tile_m, tile_n, landed):
-    """Replay tile landings (issue indices, in landing order) through the tracker (Sec. 4.2)."""
+def track(M, N, P, r, tile_m, tile_n, landed, updates=None):
+    """Replay tile landings (issue indices, in landing order) through the tracker (Sec. 4.2).
+    updates: per chunk, the updates expected per element (threshold = tiles per chunk x that;
+    Sec. 4.2.1: 2 for a ring reduce-scatter chunk that also receives the upstream update)."""
     landed = np.ascontiguousarray(landed, dtype=np.int64)
+    upd = None if updates is None else np.ascontiguousarray(updates, dtype=np.int32)
     counter = np.zeros(P, dtype=np.uint32)
     ready = np.zeros(P, dtype=np.uint32)
     queue = np.zeros(P, dtype=np.uint32)
     qlen = ctypes.c_uint32(0)
-    _check(lib().t3o_track(M, N, P, r, tile_m, tile_n, _ptr(landed), landed.shape[0],
-                           _ptr(counter), _ptr(ready), _ptr(queue), ctypes.byref(qlen)), "track")
+    _check(lib().t3o_track_upd(M, N, P, r, tile_m, tile_n, _ptr(upd), _ptr(landed),
+                               landed.shape[0], _ptr(counter), _ptr(ready), _ptr(queue),
+                               ctypes.byref(qlen)), "track")
     return {"counter": counter, "ready": ready, "queue": queue, "queue_len": int(qlen.value)}
 
 
@@ -155,7 +161,7 @@ def executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin=0):
 
 def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
                tile_limit=-1, tile_begin=0, step0_store_only=False, fwd_direct=False,
-               fwd_init=None):
+               fwd_init=None, two_writers=False, R_init=None):
     """The whole path for one rank, by the definition.
 
     Returns a dict with
@@ -179,6 +185,9 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
     C = gemm_rows(A_bits, B_bits, b_layout)
     S = reduce_rows(C, incoming, P, skip_chunk=int(order[0]) if step0_store_only else -1)
     mask, L, B0 = executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin)
+    if two_writers:
+        return _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0,
+                            order, own, step0_store_only, fwd_init, R_init)
     trk = track(M, N, P, r, tile_m, tile_n, np.arange(B0, L, dtype=np.int64))
 
     fwd = (np.zeros((max(P - 1, 0), M, W), dtype=np.float32) if fwd_init is None
@@ -198,3 +207,44 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
     out.update(R=R, fwd=fwd, owned=R[:, own * W:(own + 1) * W].copy(), order=order, own=own,
                tiles_per_chunk=tiles_per_chunk(M, N, P, tile_m, tile_n), executed=L - B0)
     return out
+
+
+def _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0, order, own,
+                 step0_store_only, fwd_init, R_init):
+    """Both writers add into R over the tiles [B0, L).  R_init must be zero on executed tiles:
+    then 0 + x is exact and the second add rounds once, whichever writer comes first, so the
+    result is S = fl32(incoming + C) either way (the sums of reduce_rows)."""
+    M, N = incoming.shape
+    W = N // P
+    R = np.zeros((M, N), np.float32) if R_init is None else np.array(R_init, np.float32, copy=True)
+    if np.any(R[mask] != 0):
+        raise ValueError("two-writer oracle needs R_init == 0 on the executed tiles")
+    R[mask] = S[mask]
+    upd = np.full(P, 2, dtype=np.int32)
+    landed = list(range(B0, L))                       # the local GEMM's tiles
+    tpc = tiles_per_chunk(M, N, P, tile_m, tile_n)
+    if step0_store_only:
+        upd[order[0]] = 1
+        landed += [t for t in range(B0, L) if t >= tpc]   # upstream skips the first chunk
+    else:
+        landed += list(range(B0, L))
+    trk = track(M, N, P, r, tile_m, tile_n, np.array(landed, dtype=np.int64), updates=upd)
+    fwd = (np.zeros((max(P - 1, 0), M, W), dtype=np.float32) if fwd_init is None
+           else np.array(fwd_init, dtype=np.float32, copy=True))
+    out = dict(trk)
+    out.update(R=R, fwd=fwd, owned=R[:, own * W:(own + 1) * W].copy(), order=order, own=own,
+               tiles_per_chunk=tpc, executed=L - B0, updates=upd)
+    return out
+
+
+def release_ready(R, fwd, ready, P, r):
+    """The triggered transfers (Sec. 4.2.2): every forwarded chunk whose ready flag is set is
+    copied from R into its forward slot.  Returns the new fwd."""
+    order, own = chunk_order(P, r)
+    W = R.shape[1] // P
+    fwd = np.array(fwd, dtype=np.float32, copy=True)
+    for s in range(P - 1):
+        c = int(order[s])
+        if ready[c]:
+            fwd[s] = R[:, c * W:(c + 1) * W]
+    return fwd

@@ -16,9 +16,11 @@ T3_ERR_NULL, T3_ERR_BAD_SHAPE, T3_ERR_BAD_TILE, T3_ERR_ALIGN, T3_ERR_UNSUPPORTED
 T3_B_NK, T3_B_KN = 0, 1
 T3_FLAG_STEP0_STORE_ONLY = 1
 T3_FLAG_FWD_DIRECT = 2
+T3_FLAG_TWO_WRITERS = 4
 
 EXPORTS = ["t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
            "t3_track_words", "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
+           "t3_upstream_update", "t3_release_chunks",
            "t3_status_string", "t3_last_hip_error"]
 
 
@@ -66,11 +68,14 @@ def lib():
         L.t3_gemm_rs_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp]
         L.t3_gemm.argtypes = [pp, vp, vp, vp, vp]
         L.t3_rs_reduce.argtypes = [pp, vp, vp, vp, vp, vp]
+        L.t3_upstream_update.argtypes = [pp, vp, vp, vp, vp]
+        L.t3_release_chunks.argtypes = [pp, vp, vp, vp, vp]
         L.t3_status_string.argtypes = [ctypes.c_int]
         L.t3_status_string.restype = ctypes.c_char_p
         L.t3_last_hip_error.restype = i32
         for f in ("t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
-                  "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce"):
+                  "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
+                  "t3_upstream_update", "t3_release_chunks"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -170,6 +175,16 @@ def t3_gemm(p, A, B, C, stream=None):
 def t3_rs_reduce(p, C, R, fwd, track, stream=None):
     _check(lib().t3_rs_reduce(ctypes.byref(p), _dptr(C), _dptr(R), _dptr(fwd), _dptr(track),
                               _stream(stream)), "t3_rs_reduce")
+
+
+def t3_upstream_update(p, incoming, R, track, stream=None):
+    _check(lib().t3_upstream_update(ctypes.byref(p), _dptr(incoming), _dptr(R), _dptr(track),
+                                    _stream(stream)), "t3_upstream_update")
+
+
+def t3_release_chunks(p, R, fwd, track, stream=None):
+    _check(lib().t3_release_chunks(ctypes.byref(p), _dptr(R), _dptr(fwd), _dptr(track),
+                                   _stream(stream)), "t3_release_chunks")
 
 
 def read_track(track, tp):

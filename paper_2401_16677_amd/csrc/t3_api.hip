@@ -65,7 +65,8 @@ t3_status resolve_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
 
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
-enum Need { kNeedAB = 1, kNeedR = 2, kNeedC = 4, kNeedFwd = 8, kNeedTrack = 16 };
+enum Need { kNeedAB = 1, kNeedR = 2, kNeedC = 4, kNeedFwd = 8, kNeedTrack = 16,
+            kNeedTwoWriters = 32 /* the call exists only in two-writer mode */ };
 
 // Validates everything and fills the plan.  *empty is set when there is nothing to launch.
 t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B, const float *C,
@@ -77,12 +78,20 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   if (st != T3_OK) return st;
   const bool fused_like = (need & kNeedTrack) != 0;
   const bool direct = fused_like && (p->flags & T3_FLAG_FWD_DIRECT);
+  const bool two_writers = fused_like && (p->flags & T3_FLAG_TWO_WRITERS);
   if ((need & kNeedAB) && (!A || !B)) return T3_ERR_NULL;
   if ((need & kNeedR) && !R) return T3_ERR_NULL;
   if ((need & kNeedC) && !C) return T3_ERR_NULL;
   if ((need & kNeedTrack) && !track) return T3_ERR_NULL;
-  if ((need & kNeedFwd) && p->tp > 1 && !fwd) return T3_ERR_NULL;
-  if (p->flags & ~(T3_FLAG_STEP0_STORE_ONLY | T3_FLAG_FWD_DIRECT)) return T3_ERR_UNSUPPORTED;
+  if ((need & kNeedFwd) && p->tp > 1 && !fwd && !(two_writers && (need & kNeedAB)))
+    return T3_ERR_NULL;                         // (the fused call releases nothing with two writers)
+  if (p->flags & ~(T3_FLAG_STEP0_STORE_ONLY | T3_FLAG_FWD_DIRECT | T3_FLAG_TWO_WRITERS))
+    return T3_ERR_UNSUPPORTED;
+  if (two_writers && direct) return T3_ERR_UNSUPPORTED;   // both writers must target R
+  if ((need & kNeedTwoWriters) && !two_writers) return T3_ERR_UNSUPPORTED;
+  // the unfused reduction kernel has no second writer to wait for
+  if (two_writers && (need & kNeedC) && (need & kNeedFwd) && !(need & kNeedTwoWriters))
+    return T3_ERR_UNSUPPORTED;
 
   const int64_t W = p->N / p->tp;
   if (need & kNeedAB) {
@@ -158,7 +167,7 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // Release workgroups (default release mode only): `agents` per forwarded chunk, placed in
   // the grid `lag` stages after the chunk's own tiles, far enough that those tiles have been
   // dispatched and are mostly finished when the release workgroups start.
-  q.agents = (fused_like && !direct && p->tp > 1) ? T3_AGENTS : 0;
+  q.agents = (fused_like && !direct && !two_writers && p->tp > 1) ? T3_AGENTS : 0;
   const int64_t resident = (*tm == 128 && *tn == 128) ? 512 : 256;   // tile workgroups the chip holds
   q.lag = (int32_t)(ceil_div(resident, tpc > 0 ? tpc : 1) + 1);
   if (q.lag > p->tp) q.lag = p->tp;
@@ -197,6 +206,15 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   for (int64_t s = 0; s + 1 < p->tp; ++s)
     if (s * tpc >= q.begin && (s + 1) * tpc <= q.limit && tpc > 0) ++released;
   q.expected_done = (int32_t)((q.limit - q.begin) + q.agents * released);
+  // updates expected per element (Sec. 4.2.1): with two writers the launches of both count in
+  // one bank, which closes when the tiles of both have been counted
+  q.upd_first = q.upd_rest = 1;
+  if (two_writers) {
+    q.upd_rest = 2;
+    q.upd_first = (p->flags & T3_FLAG_STEP0_STORE_ONLY) ? 1 : 2;
+    const int64_t up_begin = (q.upd_first == 1 && q.begin < tpc) ? (tpc < q.limit ? tpc : q.limit) : q.begin;
+    q.expected_done = (int32_t)((q.limit - q.begin) + (q.limit - up_begin));
+  }
   q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
   q.resident = (int32_t)resident;
   return T3_OK;
@@ -353,6 +371,45 @@ t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd
     hipLaunchKernelGGL((t3k::reduce_tile_kernel<128, 256>), grid, block, 0, s, q);
   else
     hipLaunchKernelGGL((t3k::reduce_tile_kernel<128, 128>), grid, block, 0, s, q);
+  return launched();
+}
+
+t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *R,
+                             uint32_t *track, void *stream) {
+  t3k::Plan q;
+  int32_t tm, tn;
+  bool empty = false;
+  const t3_status st = make_plan(p, kNeedC | kNeedR | kNeedTrack | kNeedTwoWriters, nullptr, nullptr,
+                                 incoming, R, nullptr, track, &q, &tm, &tn, &empty);
+  if (st != T3_OK) return st;
+  if (empty) return T3_OK;
+  const dim3 grid(grid_size(q)), block(t3k::kThreads);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (tm == 256 && tn == 256)
+    hipLaunchKernelGGL((t3k::upstream_update_kernel<256, 256>), grid, block, 0, s, q);
+  else if (tm == 256 && tn == 128)
+    hipLaunchKernelGGL((t3k::upstream_update_kernel<256, 128>), grid, block, 0, s, q);
+  else if (tm == 128 && tn == 256)
+    hipLaunchKernelGGL((t3k::upstream_update_kernel<128, 256>), grid, block, 0, s, q);
+  else
+    hipLaunchKernelGGL((t3k::upstream_update_kernel<128, 128>), grid, block, 0, s, q);
+  return launched();
+}
+
+t3_status t3_release_chunks(const t3_problem *p, const float *R, float *fwd,
+                            const uint32_t *track, void *stream) {
+  t3k::Plan q;
+  int32_t tm, tn;
+  bool empty = false;
+  const t3_status st = make_plan(p, kNeedR | kNeedFwd | kNeedTrack | kNeedTwoWriters, nullptr,
+                                 nullptr, nullptr, const_cast<float *>(R), fwd,
+                                 const_cast<uint32_t *>(track), &q, &tm, &tn, &empty);
+  if (st != T3_OK) return st;
+  if (p->tp < 2 || p->M == 0 || p->N == 0) return T3_OK;
+  q.agents = T3_AGENTS;
+  q.rows_per_agent = (int32_t)ceil_div(p->M, q.agents);
+  hipLaunchKernelGGL(t3k::release_ready_kernel, dim3((unsigned)(q.agents * (p->tp - 1))),
+                     dim3(t3k::kThreads), 0, static_cast<hipStream_t>(stream), q);
   return launched();
 }
 

@@ -38,6 +38,7 @@ constexpr int kSpinLimit = 1 << 22;   // polls of a release workgroup before it 
 
 constexpr uint32_t kFlagStep0StoreOnly = 1u;
 constexpr uint32_t kFlagFwdDirect = 2u;
+constexpr uint32_t kFlagTwoWriters = 4u;
 
 enum Mode { kModeGemm = 0, kModeFused = 1 };
 enum Role { kRoleNone = 0, kRoleTile = 1, kRoleRelease = 2 };
@@ -66,6 +67,7 @@ struct Plan {
   int32_t expected_done;               // grid positions of this launch that do work
   int32_t total_blocks;                // grid positions (tiles and release work) of the launch
   int32_t resident;                    // tile workgroups the chip holds at once
+  int32_t upd_first, upd_rest;         // updates expected per element of chunk order[0] / the others
   int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
   uint32_t flags;
 };
@@ -227,7 +229,9 @@ __device__ inline void track_count(const Plan &p, const Trk &t, int c) {
     const uint32_t old = __hip_atomic_fetch_add(&t.counter[c], 1u, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
     const uint32_t d = __hip_atomic_fetch_add(t.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old + 1u == (uint32_t)p.tpc) {   // the landing that reaches the threshold triggers
+    // threshold = tracked regions of the chunk x updates expected per element (Sec. 4.2.1)
+    const uint32_t threshold = (uint32_t)p.tpc * (uint32_t)(c == p.rank ? p.upd_first : p.upd_rest);
+    if (old + 1u == threshold) {         // the landing that reaches the threshold triggers
       if (c != p.own) {
         const uint32_t pos = __hip_atomic_fetch_add(t.queue_len, 1u, __ATOMIC_RELAXED,
                                                     __HIP_MEMORY_SCOPE_AGENT);
@@ -460,9 +464,10 @@ void gemm_tile_kernel(const Plan p) {
   // of the wavefront tile.  Per 16-byte access 4 lanes cover 64 contiguous bytes of a row.
   const bool store_only = (MODE == kModeGemm) || ((p.flags & kFlagStep0StoreOnly) && tl.s == 0);
   const bool to_fwd = (MODE == kModeFused) && (p.flags & kFlagFwdDirect) && tl.c != p.own;
+  // two writers (Sec. 4.1): the tile is ADDED into R with atomics, as the upstream update is
+  const bool two_writers = (MODE == kModeFused) && (p.flags & kFlagTwoWriters);
   const int rw0 = m0 + wm * WM, cw0 = n0 + wn * WN;          // wavefront tile origin (uniform)
   const bool full = (rw0 + WM <= p.M) && (cw0 + WN <= col_hi);
-  const int lrow = rw0 + fr, lcol = cw0 + 4 * fq;            // this lane's row / first column, block (0,0)
   // ---- "pairs".  Global accesses that touch half a 128-byte line per row (what one 16 x 16
   // block in the accumulator layout amounts to) run at a third of the rate of full lines, so
   // the incoming partial and the results move in units of one PAIR = two neighbouring blocks =
@@ -500,7 +505,7 @@ void gemm_tile_kernel(const Plan p) {
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (MODE == kModeFused && !store_only) {
+  if (MODE == kModeFused && !store_only && !two_writers) {
     // The incoming partial, loaded before the main loop: every pair as two full-line accesses
     // (8 rows x 128 bytes), all in flight together, landing in the pair's accumulator registers;
     // then pair by pair through LDS into the accumulator layout.  The scratch is the last
@@ -673,8 +678,17 @@ void gemm_tile_kernel(const Plan p) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane * 16);
-      if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
-        store_agent(out_rsrc, out_u[h], ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u, v);
+      if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi)) {
+        const uint32_t blk_off = ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u;
+        if (two_writers) {       // op-and-store (Sec. 4.3): the other writer adds into the same words
+          float *dst = (float *)((char *)const_cast<float *>(out_base) + blk_off + out_u[h]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            __hip_atomic_fetch_add(dst + e, v[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+          store_agent(out_rsrc, out_u[h], blk_off, v);
+        }
+      }
     }
     // keep the scheduler from running many pairs ahead: it would park their values in registers
     if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
@@ -724,6 +738,57 @@ __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
     store_agent((f32x4 *)(out_base + row * ld_out) + cc, v);
   }
   track_tile(p, trk, tl.c);
+}
+
+// The upstream neighbour's updates (the DMA updates of Sec. 4.1), stood in for on one GPU:
+// `incoming` (p.C) is added into R tile by tile with the same op-and-store atomics as the local
+// GEMM's tiles, in the same issue order, and every tile is counted in the same tracker.  With
+// the first chunk stored only (Sec. 4.4) it has no upstream update: those tiles are skipped.
+template <int BM, int BN>
+__global__ __launch_bounds__(kThreads) void upstream_update_kernel(const Plan p) {
+  Tile tl;
+  int slot = 0, agent = 0;
+  if (decode_block(p, blockIdx.x, tl, slot, agent) != kRoleTile) return;
+  if ((p.flags & kFlagStep0StoreOnly) && tl.s == 0) return;
+  const Trk trk = trk_open(p);
+  const int m0 = tl.mi * BM;
+  const int col_lo = tl.c * p.W;
+  const int n0 = col_lo + tl.nj * BN;
+  const int rows = min(BM, p.M - m0);
+  const int cols4 = min(BN, col_lo + p.W - n0) >> 2;
+  const int total = rows * cols4;
+  for (int e = threadIdx.x; e < total; e += kThreads) {
+    const int rr = e / cols4, cc = e - rr * cols4;
+    const int64_t row = m0 + rr;
+    const f32x4 v = __builtin_nontemporal_load((const f32x4 *)(p.C + row * p.ldc + n0) + cc);
+    float *dst = p.R + row * p.ldr + n0 + 4 * cc;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      __hip_atomic_fetch_add(dst + q, v[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  track_tile(p, trk, tl.c);
+}
+
+// The triggered transfers, as a launch of their own (two-writer mode, where no launch can wait
+// for the other writer): workgroup (slot, agent) copies its rows of chunk order[slot] into the
+// forward slot if the chunk's ready flag is set in the bank of the launch that last completed.
+__global__ __launch_bounds__(kThreads) void release_ready_kernel(const Plan p) {
+  const int slot = blockIdx.x / p.agents, agent = blockIdx.x % p.agents;
+  if (slot > p.P - 2) return;
+  const uint32_t g = __builtin_amdgcn_readfirstlane(__hip_atomic_load(
+      p.track + 2 * trk_bank_words(p.P), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  const uint32_t *bank = p.track + ((g + 1u) & 1u) * trk_bank_words(p.P);   // bank (g - 1) & 1
+  int c = p.rank + slot;
+  if (c >= p.P) c -= p.P;
+  if (__hip_atomic_load(bank + p.P + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int W4 = p.W >> 2;
+  const int r_end = min(p.M, (agent + 1) * p.rows_per_agent);
+  for (int r = agent * p.rows_per_agent + wave; r < r_end; r += kThreads / 64) {
+    const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
+    f32x4 *dst = (f32x4 *)(p.fwd + ((int64_t)slot * p.M + r) * p.W);
+    for (int c0 = lane; c0 < W4; c0 += 64) dst[c0] = __builtin_nontemporal_load(src + c0);
+  }
 }
 
 // Clears tracker state: both banks (queue entries to empty, the rest to 0), gen and error to 0.

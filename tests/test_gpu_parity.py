@@ -188,6 +188,88 @@ def test_ring_of_virtual_ranks_closes_on_unsliced_gemm(gpu, oracle, kind):
             assert e <= EXPECT
 
 
+def _run_two_writers(gpu, a, b, inc, tp, rank, tile, *, order, step0=False, tile_begin=0, tile_limit=-1):
+    """Two-writer mode through the C ABI: the fused call and the upstream update, one after the
+    other in either order or on two streams at once, then the triggered transfers."""
+    import torch
+    M, K = a.shape
+    N = b.shape[0]
+    W = N // tp
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    INC = torch.from_numpy(inc).to(dev)
+    R = torch.zeros((M, N), dtype=torch.float32, device=dev)
+    fwd = torch.full((tp - 1, M, W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+    track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+    flags = t3.T3_FLAG_TWO_WRITERS | (t3.T3_FLAG_STEP0_STORE_ONLY if step0 else 0)
+    p = t3.problem(M, N, K, tp, rank, *tile, ldc=N, flags=flags, tile_begin=tile_begin,
+                   tile_limit=tile_limit)
+    t3.t3_track_reset(tp, track)
+    torch.cuda.synchronize()
+    if order == "local_first":
+        t3.t3_gemm_rs_fused(p, A, B, R, None, track)
+        t3.t3_upstream_update(p, INC, R, track)
+    elif order == "upstream_first":
+        t3.t3_upstream_update(p, INC, R, track)
+        t3.t3_gemm_rs_fused(p, A, B, R, None, track)
+    else:                                   # at the same time, on two streams
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        with torch.cuda.stream(s1):
+            t3.t3_gemm_rs_fused(p, A, B, R, None, track)
+        with torch.cuda.stream(s2):
+            t3.t3_upstream_update(p, INC, R, track)
+    torch.cuda.synchronize()
+    tr = t3.read_track(track, tp)
+    t3.t3_release_chunks(p, R, fwd, track)
+    torch.cuda.synchronize()
+    return R.cpu().numpy(), fwd.cpu().numpy(), tr
+
+
+@pytest.mark.parametrize("order", ["local_first", "upstream_first", "concurrent"])
+@pytest.mark.parametrize("step0", [False, True])
+@pytest.mark.parametrize("case", [(300, 800, 200, 4, 2, (128, 128)), (600, 1280, 1160, 2, 0, (256, 256)),
+                                  (1024, 4096, 512, 4, 1, (256, 256)), (520, 1056, 72, 2, 1, (256, 128))])
+def test_two_writers_bit_exact(gpu, oracle, case, step0, order):
+    """Sec. 4.1 / 4.2.1: the local GEMM's tiles and the upstream update are both added into R with
+    atomics; every element gets two updates, a chunk triggers after both writers' tiles."""
+    M, N, K, tp, rank, tile = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=300 + M)
+    print(f"case={case} step0={step0} order={order}", flush=True)
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, two_writers=True, step0_store_only=step0,
+                             fwd_init=sent)
+    R, fwd, tr = _run_two_writers(gpu, a, b, inc, tp, rank, tile, order=order, step0=step0)
+    assert np.array_equal(R, want["R"])
+    assert np.array_equal(tr["counter"], want["counter"]) and np.array_equal(tr["ready"], want["ready"])
+    assert tr["queue_len"] == want["queue_len"] == tp - 1 and tr["error"] == 0 and tr["gen"] == 1
+    assert set(tr["queue"][:tp - 1].tolist()) == set(want["queue"][:tp - 1].tolist())
+    assert np.array_equal(fwd, oracle.release_ready(want["R"], sent, want["ready"], tp, rank))
+
+
+def test_two_writers_one_ring_step_and_float(gpu, oracle):
+    """A tile range (ring step 1) with two writers: only that chunk triggers; and normal inputs
+    within the floating-point bar."""
+    M, N, K, tp, rank, tile = 512, 2048, 320, 4, 3, (256, 256)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=17)
+    tpc = oracle.tiles_per_chunk(M, N, tp, *tile)
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, two_writers=True, tile_begin=tpc,
+                             tile_limit=2 * tpc, fwd_init=sent)
+    R, fwd, tr = _run_two_writers(gpu, a, b, inc, tp, rank, tile, order="concurrent",
+                                  tile_begin=tpc, tile_limit=2 * tpc)
+    assert np.array_equal(R, want["R"])
+    assert np.array_equal(tr["counter"], want["counter"]) and np.array_equal(tr["ready"], want["ready"])
+    assert tr["queue_len"] == 1 and tr["ready"].sum() == 1
+    assert np.array_equal(fwd, oracle.release_ready(want["R"], sent, want["ready"], tp, rank))
+    w = wl.make_shape("two", 1024, 4096, 1024, 4, 1, 256, 256)
+    a, b, inc = wl.make_inputs(w, seed=18)
+    want = oracle.fused_path(a, b, inc, 4, 1, 256, 256, two_writers=True)
+    R, fwd, tr = _run_two_writers(gpu, a, b, inc, 4, 1, (256, 256), order="concurrent")
+    e = gpu.rel_err(R, want["R"])
+    print(f"two writers, normal inputs: normwise error {e:.2e}", flush=True)
+    assert e <= EXPECT and np.all(tr["ready"] == 1)
+
+
 def test_tiny_outproj_config_float_parity(gpu, oracle):
     w = wl.WORKLOADS["tiny_outproj"]
     a, b, inc = wl.make_inputs(w)

@@ -99,6 +99,20 @@ def test_bad_arguments_are_refused_before_any_launch():
     # R of 4 GiB or more (32-bit byte offsets in the kernels): refused, nothing launched
     big = dict(M=65536, N=16384, K=64, tp=4, rank=0, tile_m=256, tile_n=256)
     assert _fused_status(t3.problem(**big)) == t3.T3_ERR_UNSUPPORTED
+    # two writers: not with the direct release; the upstream / release calls need the flag
+    assert _fused_status(t3.problem(**ok, flags=t3.T3_FLAG_TWO_WRITERS | t3.T3_FLAG_FWD_DIRECT)) == \
+        t3.T3_ERR_UNSUPPORTED
+    vp = ctypes.c_void_p
+    pw = t3.problem(**ok)
+    assert L.t3_upstream_update(ctypes.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
+        t3.T3_ERR_UNSUPPORTED
+    assert L.t3_release_chunks(ctypes.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
+        t3.T3_ERR_UNSUPPORTED
+    pw = t3.problem(**ok, flags=t3.T3_FLAG_TWO_WRITERS)
+    assert L.t3_upstream_update(ctypes.byref(pw), vp(0), vp(FAKE), vp(FAKE), vp(0)) == t3.T3_ERR_NULL
+    assert L.t3_release_chunks(ctypes.byref(pw), vp(FAKE), vp(0), vp(FAKE), vp(0)) == t3.T3_ERR_NULL
+    assert L.t3_rs_reduce(ctypes.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
+        t3.T3_ERR_UNSUPPORTED
     # empty problems are fine and launch nothing
     assert _fused_status(t3.problem(**{**ok, "M": 0})) == t3.T3_OK
     assert _fused_status(t3.problem(**{**ok, "N": 0})) == t3.T3_OK

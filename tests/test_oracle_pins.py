@@ -257,6 +257,50 @@ def test_ring_steps_as_tile_ranges_compose_to_the_whole_path(oracle, P):
                               whole[:, own * W:(own + 1) * W].astype(np.float32))
 
 
+def test_two_writers_threshold_and_order_invariance(oracle):
+    """Sec. 4.2.1: a ring reduce-scatter chunk expects 2 updates per element (local GEMM +
+    upstream DMA), so its threshold is 2 x tiles-per-chunk (the paper's figure, from the golden
+    map); the trigger fires on the LAST of them, whichever writer it is and however the two
+    interleave; with the first chunk stored only, that chunk expects 1."""
+    M, N, K, P, r, tm, tn = 10, 12, 16, 3, 1, 4, 2
+    upe = int(_golden_map()["updates_per_element_ring_rs"])
+    assert upe == 2
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=91)
+    tpc = oracle.tiles_per_chunk(M, N, P, tm, tn)
+    T = P * tpc
+    one = oracle.fused_path(a, b, inc, P, r, tm, tn)
+    two = oracle.fused_path(a, b, inc, P, r, tm, tn, two_writers=True)
+    assert np.array_equal(two["R"], one["R"])            # same sums, whichever writer is first
+    assert np.all(two["counter"] == upe * tpc) and np.all(two["ready"] == 1)
+    assert two["queue_len"] == P - 1 and np.all(two["fwd"] == 0)
+    # only one writer's tiles: nothing is ready
+    half = oracle.track(M, N, P, r, tm, tn, np.arange(T), updates=[upe] * P)
+    assert np.all(half["counter"] == tpc) and not half["ready"].any() and half["queue_len"] == 0
+    # random interleavings of the two writers: same final state, and the trigger position is
+    # exactly where the chunk's last update lands
+    rng = np.random.default_rng(5)
+    for _ in range(20):
+        landed = rng.permutation(np.concatenate([np.arange(T), np.arange(T)]))
+        full = oracle.track(M, N, P, r, tm, tn, landed, updates=[upe] * P)
+        assert np.array_equal(full["counter"], two["counter"]) and np.all(full["ready"] == 1)
+        assert set(full["queue"][:P - 1]) == set(two["queue"][:P - 1])
+        c0 = int(full["queue"][0])                       # first chunk to trigger
+        s0 = (c0 - r) % P
+        last = max(i for i, t in enumerate(landed) if t // tpc == s0)
+        before = oracle.track(M, N, P, r, tm, tn, landed[:last], updates=[upe] * P)
+        assert before["ready"][c0] == 0
+        assert oracle.track(M, N, P, r, tm, tn, landed[:last + 1], updates=[upe] * P)["ready"][c0] == 1
+    # first chunk stored only: one update there, the upstream writer skips it
+    st = oracle.fused_path(a, b, inc, P, r, tm, tn, two_writers=True, step0_store_only=True)
+    ref = oracle.fused_path(a, b, inc, P, r, tm, tn, step0_store_only=True)
+    assert np.array_equal(st["R"], ref["R"])
+    assert st["counter"][r] == tpc and np.all(np.delete(st["counter"], r) == 2 * tpc)
+    assert np.all(st["ready"] == 1)
+    # the triggered transfers
+    fwd = oracle.release_ready(two["R"], two["fwd"], two["ready"], P, r)
+    assert np.array_equal(fwd, one["fwd"])
+
+
 # ---------------------------------------------------------------- tiles, tracker, prefixes
 
 @pytest.mark.parametrize("M,N,P,r,tm,tn", [(8, 12, 3, 1, 4, 2), (10, 12, 2, 0, 4, 4),
