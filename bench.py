@@ -98,6 +98,7 @@ def main():
     track = torch.zeros(t3.t3_track_words(w.tp), dtype=torch.int32, device=dev)
     flags = t3.T3_FLAG_FWD_DIRECT if args.direct else 0
     p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n, flags=flags)
+    tile = (w.tile_m, w.tile_n) if w.tile_m else t3.t3_default_tile(p)
 
     t3.t3_track_reset(w.tp, track)       # once: every launch leaves a clean bank for the next
 
@@ -198,7 +199,7 @@ def main():
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS,
                 "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.release))}
-    roof.update(kernel="gemm_tile_kernel<%d,%d,fused>" % (w.tile_m, w.tile_n),
+    roof.update(kernel="gemm_tile_kernel<%d,%d,fused>" % tuple(tile),
                 kernel_ms_avg=k_avg, kernel_ms_min=k_ms[0], kernel_ms_median=k_ms[len(k_ms) // 2],
                 algorithmic_bytes=bytes_alg, flop=w.flop)
 
@@ -208,7 +209,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": t_fused * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "tp": w.tp, "rank": w.rank,
-                   "tile": [w.tile_m, w.tile_n],
+                   "tile": list(tile),
                    "release": "direct" if args.direct else "copy",
                    "launch": "hip_graph" if args.graph else "eager"},
         "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,

@@ -38,18 +38,27 @@ bool tile_supported(int32_t tm, int32_t tn) {
 }
 
 void default_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
-  // the largest tile that still gives every compute unit a workgroup, else the smallest
+  // Cheapest shape by (work padded up to whole tiles) x (how much slower than the 256 x 256
+  // tile the shape's main loop runs per flop) x (how far the tiles fall short of filling the
+  // chip's 256 compute units).
+  static const double kSlower[kNumTileShapes] = {1.0, 1.28, 1.28, 1.45};
   const int64_t W = p->N / p->tp;
-  for (int i = 0; i < kNumTileShapes; ++i) {
-    const int64_t T = ceil_div(p->M, kTileShapes[i].m) * ceil_div(W, kTileShapes[i].n) * p->tp;
-    if (T >= 256) {
-      *tm = kTileShapes[i].m;
-      *tn = kTileShapes[i].n;
-      return;
-    }
-  }
+  double best = -1.0;
   *tm = 128;
   *tn = 128;
+  for (int i = 0; i < kNumTileShapes; ++i) {
+    const int64_t Mt = ceil_div(p->M, kTileShapes[i].m), Wt = ceil_div(W, kTileShapes[i].n);
+    const int64_t T = Mt * Wt * p->tp;
+    if (T == 0) continue;
+    const double padded = (double)(Mt * kTileShapes[i].m) * (double)(Wt * kTileShapes[i].n) /
+                          ((double)p->M * (double)W);
+    const double score = padded * kSlower[i] * (T < 256 ? 256.0 / (double)T : 1.0);
+    if (best < 0 || score < best) {
+      best = score;
+      *tm = kTileShapes[i].m;
+      *tn = kTileShapes[i].n;
+    }
+  }
 }
 
 t3_status resolve_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {

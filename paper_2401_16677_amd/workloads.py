@@ -47,8 +47,22 @@ WORKLOADS = {
     "gpt3_fc2": Workload("gpt3_fc2", 4096, 12288, 6144, 8, 5, 256, 256, a_dist="halfnormal",
                          index=2),
     "wide_fc2": Workload("wide_fc2", 2048, 20480, 10240, 8, 7, 128, 256, index=3),
-    "hightp_outproj": Workload("hightp_outproj", 8192, 18432, 1152, 16, 9, 256, 128, index=4),
+    "hightp_outproj": Workload("hightp_outproj", 8192, 18432, 1152, 16, 9, 256, 256, index=4),
 }
+
+
+# Further shapes: row-parallel sub-layers of the models the paper evaluates (its Table 2: hidden
+# size H, tokens = sequence length x batch, TP degree), K = H/TP for the output projection and
+# 4H/TP for FC-2.  tile 0 x 0 = the library's default tile for the shape.
+PAPER_SHAPES = {
+    "megagpt2_fc2_tp8": Workload("megagpt2_fc2_tp8", 16384, 3072, 1536, 8, 2, 0, 0, index=10),
+    "megagpt2_outproj_tp16": Workload("megagpt2_outproj_tp16", 16384, 3072, 192, 16, 11, 0, 0, index=11),
+    "tnlg_fc2_tp8": Workload("tnlg_fc2_tp8", 8192, 4256, 2128, 8, 6, 0, 0, a_dist="halfnormal", index=12),
+    "gpt3_fc2_tp32": Workload("gpt3_fc2_tp32", 2048, 12288, 1536, 32, 17, 0, 0, index=13),
+    "palm_outproj_tp32": Workload("palm_outproj_tp32", 2048, 18432, 576, 32, 30, 0, 0, index=14),
+    "mtnlg_fc2_tp32": Workload("mtnlg_fc2_tp32", 2048, 20480, 2560, 32, 5, 0, 0, index=15),
+}
+WORKLOADS.update(PAPER_SHAPES)
 
 
 def f32_to_bf16_bits(x):

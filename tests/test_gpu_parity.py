@@ -398,6 +398,45 @@ def test_full_size_sampled_rows(gpu, oracle, name, direct):
     assert bool(torch.isfinite(fwd).all()) and not bool((fwd == gpu.SENTINEL).all(dim=2).any())
 
 
+@pytest.mark.parametrize("name", sorted(wl.PAPER_SHAPES))
+def test_paper_table2_shapes_sampled_rows(gpu, oracle, name):
+    """Sub-layer shapes of the paper's Table 2 models with the library's default tile, direct
+    release: sampled rows against the oracle (ragged chunk widths, TP up to 32)."""
+    import torch
+    w = wl.WORKLOADS[name]
+    a, b, inc = wl.make_inputs(w)
+    p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, flags=t3.T3_FLAG_FWD_DIRECT)
+    tm, tn = t3.t3_default_tile(p)
+    print(f"workload={name} default tile={tm}x{tn} W={w.W}", flush=True)
+    rng = np.random.default_rng(w.seed)
+    rows = np.array(sorted({0, w.M - 1} | set(rng.integers(0, w.M, 24).tolist())), dtype=np.int32)
+    S = oracle.reduce_rows(oracle.gemm_rows(a, b, rows=rows), inc, w.tp, rows=rows)
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    R = torch.from_numpy(inc).to(dev)
+    fwd = torch.full((w.tp - 1, w.M, w.W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(w.tp), dtype=torch.int32, device=dev)
+    t3.t3_track_reset(w.tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+    order, own = oracle.chunk_order(w.tp, w.rank)
+    tr = t3.read_track(track, w.tp)
+    assert np.all(tr["counter"] == oracle.tiles_per_chunk(w.M, w.N, w.tp, tm, tn))
+    assert np.all(tr["ready"] == 1) and tr["queue_len"] == w.tp - 1 and tr["error"] == 0
+    idx = torch.from_numpy(rows.astype(np.int64)).to(dev)
+    Rg = R.index_select(0, idx).cpu().numpy()
+    fg = fwd.index_select(1, idx).cpu().numpy()
+    W = w.W
+    errs = []
+    for s in range(w.tp):
+        c = int(order[s])
+        want = S[:, c * W:(c + 1) * W]
+        errs.append(gpu.rel_err(Rg[:, c * W:(c + 1) * W] if c == own else fg[s], want))
+    print(f"max normwise error over chunks {max(errs):.3e}", flush=True)
+    assert max(errs) <= EXPECT
+    assert not bool((fwd == gpu.SENTINEL).all(dim=2).any())
+
+
 def test_graph_replays_match_eager(gpu, oracle):
     """The step bench.py times (tracker reset + fused call) captured in a HIP graph: every
     replay, with eager work and synchronisation in between, must reproduce the eager result."""
