@@ -82,6 +82,10 @@ typedef struct {
   int64_t tile_begin;     /* tiles whose issue index is below tile_begin do not run either: with
                              tile_limit, [tile_begin, tile_limit) is a range of the issue order,
                              e.g. one ring step s = [s*tpc, (s+1)*tpc) (Sec. 4.1).  0 = from the start  */
+  int32_t split_k;        /* 0 or 1: one workgroup per tile.  S > 1 (two-writer mode only, S <= K/64,
+                             S <= 64): S workgroups share a tile, each multiplying a part of K and
+                             adding it into R, so the local GEMM makes S updates per element and
+                             a chunk's threshold is (S + 1) * tpc (Sec. 7.7)                        */
 } t3_problem;
 
 /*

@@ -161,7 +161,7 @@ def executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin=0):
 
 def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
                tile_limit=-1, tile_begin=0, step0_store_only=False, fwd_direct=False,
-               fwd_init=None, two_writers=False, R_init=None):
+               fwd_init=None, two_writers=False, R_init=None, split_k=1):
     """The whole path for one rank, by the definition.
 
     Returns a dict with
@@ -187,7 +187,7 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
     mask, L, B0 = executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin)
     if two_writers:
         return _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0,
-                            order, own, step0_store_only, fwd_init, R_init)
+                            order, own, step0_store_only, fwd_init, R_init, split_k)
     trk = track(M, N, P, r, tile_m, tile_n, np.arange(B0, L, dtype=np.int64))
 
     fwd = (np.zeros((max(P - 1, 0), M, W), dtype=np.float32) if fwd_init is None
@@ -210,7 +210,7 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
 
 
 def _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0, order, own,
-                 step0_store_only, fwd_init, R_init):
+                 step0_store_only, fwd_init, R_init, split_k=1):
     """Both writers add into R over the tiles [B0, L).  R_init must be zero on executed tiles:
     then 0 + x is exact and the second add rounds once, whichever writer comes first, so the
     result is S = fl32(incoming + C) either way (the sums of reduce_rows)."""
@@ -220,11 +220,15 @@ def _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0,
     if np.any(R[mask] != 0):
         raise ValueError("two-writer oracle needs R_init == 0 on the executed tiles")
     R[mask] = S[mask]
-    upd = np.full(P, 2, dtype=np.int32)
-    landed = list(range(B0, L))                       # the local GEMM's tiles
+    if split_k < 1:
+        raise ValueError("split_k must be >= 1")
+    # (with split_k > 1 the value is still S: the parts' sum is the same product, formed in fp64
+    # here; on hardware the order of the fp32 adds is free, which the tolerance covers)
+    upd = np.full(P, split_k + 1, dtype=np.int32)
+    landed = list(range(B0, L)) * split_k             # the local GEMM's tile updates
     tpc = tiles_per_chunk(M, N, P, tile_m, tile_n)
     if step0_store_only:
-        upd[order[0]] = 1
+        upd[order[0]] = split_k
         landed += [t for t in range(B0, L) if t >= tpc]   # upstream skips the first chunk
     else:
         landed += list(range(B0, L))

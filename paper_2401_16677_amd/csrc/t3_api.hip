@@ -98,6 +98,12 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
     return T3_ERR_UNSUPPORTED;
   if (two_writers && direct) return T3_ERR_UNSUPPORTED;   // both writers must target R
   if ((need & kNeedTwoWriters) && !two_writers) return T3_ERR_UNSUPPORTED;
+  // split-K: several workgroups add into one tile, so it needs the atomic updates of two-writer
+  // mode, and every part needs at least one full K-slab of 64
+  const int32_t split_k = p->split_k > 1 ? p->split_k : 1;
+  if (p->split_k < 0) return T3_ERR_BAD_SHAPE;
+  if (split_k > 1 && fused_like && (!two_writers || split_k > p->K / 64 || split_k > 64))
+    return T3_ERR_UNSUPPORTED;
   // the unfused reduction kernel has no second writer to wait for
   if (two_writers && (need & kNeedC) && (need & kNeedFwd) && !(need & kNeedTwoWriters))
     return T3_ERR_UNSUPPORTED;
@@ -218,11 +224,15 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // updates expected per element (Sec. 4.2.1): with two writers the launches of both count in
   // one bank, which closes when the tiles of both have been counted
   q.upd_first = q.upd_rest = 1;
+  q.split_k = 1;
   if (two_writers) {
-    q.upd_rest = 2;
-    q.upd_first = (p->flags & T3_FLAG_STEP0_STORE_ONLY) ? 1 : 2;
-    const int64_t up_begin = (q.upd_first == 1 && q.begin < tpc) ? (tpc < q.limit ? tpc : q.limit) : q.begin;
-    q.expected_done = (int32_t)((q.limit - q.begin) + (q.limit - up_begin));
+    q.split_k = split_k;                        // local updates per element = parts of K (Sec. 7.7)
+    const bool step0 = (p->flags & T3_FLAG_STEP0_STORE_ONLY) != 0;
+    q.upd_rest = split_k + 1;
+    q.upd_first = split_k + (step0 ? 0 : 1);
+    const int64_t up_begin = (step0 && q.begin < tpc) ? (tpc < q.limit ? tpc : q.limit) : q.begin;
+    q.expected_done = (int32_t)((q.limit - q.begin) * split_k + (q.limit - up_begin));
+    if (T * split_k >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
   }
   q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
   q.resident = (int32_t)resident;
@@ -247,7 +257,8 @@ void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
   // its own instead: a release position may have to wait for its chunk, and a persistent
   // workgroup would sit on its later tiles meanwhile.
   const bool persistent = q.agents == 0;
-  const dim3 grid((unsigned)(persistent && q.total_blocks > q.resident ? q.resident : q.total_blocks));
+  const int64_t positions = (int64_t)q.total_blocks * (MODE == t3k::kModeFused ? q.split_k : 1);
+  const dim3 grid((unsigned)(persistent && positions > q.resident ? q.resident : positions));
   // K-slabs of 64 everywhere.  256 x 256: 8 wavefronts of 128 x 64, two 64-KiB stages; the
   // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
   // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.
@@ -349,6 +360,7 @@ t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, fl
 }
 
 t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, void *stream) {
+  // (flags and split_k are ignored: make_plan sees no tracker for this call)
   t3k::Plan q;
   int32_t tm, tn;
   bool empty = false;

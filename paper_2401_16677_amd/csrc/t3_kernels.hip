@@ -68,6 +68,7 @@ struct Plan {
   int32_t total_blocks;                // grid positions (tiles and release work) of the launch
   int32_t resident;                    // tile workgroups the chip holds at once
   int32_t upd_first, upd_rest;         // updates expected per element of chunk order[0] / the others
+  int32_t split_k;                     // >= 1: workgroups that share a tile, each taking a part of K (Sec. 7.7)
   int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
   uint32_t flags;
 };
@@ -374,7 +375,14 @@ void gemm_tile_kernel(const Plan p) {
     pending_c = -1;
   };
 
-  for (int blk = blockIdx.x; blk < p.total_blocks; blk += gridDim.x) {
+  for (int pos = blockIdx.x; pos < p.total_blocks * p.split_k; pos += gridDim.x) {
+  // split-K (two-writer mode only): `split_k` consecutive positions share a tile, part j taking
+  // K-slabs [j q, (j+1) q) of the K / 64 full ones, the last part also what is left over
+  const int blk = pos / p.split_k, part = pos - blk * p.split_k;
+  const int part_slabs = (p.K / kBK) / p.split_k;
+  const int k0 = part * part_slabs * kBK;
+  const int Kpart = (part == p.split_k - 1) ? p.K - k0 : part_slabs * kBK;
+  const char *const Ap = (const char *)p.A + (int64_t)k0 * 2, *const Bp = (const char *)p.B + (int64_t)k0 * 2;
   Tile tl;
   int slot = 0, agent = 0;
   const int role = decode_block(p, blk, tl, slot, agent);
@@ -421,8 +429,8 @@ void gemm_tile_kernel(const Plan p) {
   // (all eight wavefronts issuing all of theirs at once stalls them on the memory pipeline).
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
   auto issue_copies = [&](int kt, int stage, int q0, int q1) {
-    const char *a = (const char *)p.A + (int64_t)kt * (kBK * 2);
-    const char *b = (const char *)p.B + (int64_t)kt * (kBK * 2);
+    const char *a = Ap + (int64_t)kt * (kBK * 2);
+    const char *b = Bp + (int64_t)kt * (kBK * 2);
     const uint32_t dst = lds_base + stage * kStageBytes;
 #pragma unroll
     for (int q = 0; q < NA; ++q)
@@ -452,8 +460,8 @@ void gemm_tile_kernel(const Plan p) {
     fragB[kk] = kBOff + (wn * WN + fr) * kRowBytes + pos;
   }
 
-  const int nkf = p.K / kBK;                     // full slabs
-  const int ktail = p.K - nkf * kBK;             // leftover elements of K (a multiple of 8)
+  const int nkf = Kpart / kBK;                   // full slabs
+  const int ktail = Kpart - nkf * kBK;           // leftover elements of K (a multiple of 8)
 
   // NSTAGE-1 slabs are always in flight.  Past the last slab the copies are repeated into
   // stages nobody reads any more, so every wait below is for the same number of younger copies.
@@ -622,14 +630,14 @@ void gemm_tile_kernel(const Plan p) {
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
       uint4 v = zero;
-      if (chunk_of(BM / NW, q) * 8 < ktail) v = *(const uint4 *)((const char *)p.A + kb + offA[q]);
+      if (chunk_of(BM / NW, q) * 8 < ktail) v = *(const uint4 *)(Ap + kb + offA[q]);
       *(uint4 *)(lds + ldsA_w + q * 1024 + lane * 16) = v;
       if (q % 2 == 1) __builtin_amdgcn_sched_barrier(0);   // two loads in flight, not all: registers
     }
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       uint4 v = zero;
-      if (chunk_of(BN / NW, q) * 8 < ktail) v = *(const uint4 *)((const char *)p.B + kb + offB[q]);
+      if (chunk_of(BN / NW, q) * 8 < ktail) v = *(const uint4 *)(Bp + kb + offB[q]);
       *(uint4 *)(lds + ldsB_w + q * 1024 + lane * 16) = v;
       if (q % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }

@@ -188,7 +188,8 @@ def test_ring_of_virtual_ranks_closes_on_unsliced_gemm(gpu, oracle, kind):
             assert e <= EXPECT
 
 
-def _run_two_writers(gpu, a, b, inc, tp, rank, tile, *, order, step0=False, tile_begin=0, tile_limit=-1):
+def _run_two_writers(gpu, a, b, inc, tp, rank, tile, *, order, step0=False, tile_begin=0, tile_limit=-1,
+                     split_k=0):
     """Two-writer mode through the C ABI: the fused call and the upstream update, one after the
     other in either order or on two streams at once, then the triggered transfers."""
     import torch
@@ -203,7 +204,7 @@ def _run_two_writers(gpu, a, b, inc, tp, rank, tile, *, order, step0=False, tile
     track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
     flags = t3.T3_FLAG_TWO_WRITERS | (t3.T3_FLAG_STEP0_STORE_ONLY if step0 else 0)
     p = t3.problem(M, N, K, tp, rank, *tile, ldc=N, flags=flags, tile_begin=tile_begin,
-                   tile_limit=tile_limit)
+                   tile_limit=tile_limit, split_k=split_k)
     t3.t3_track_reset(tp, track)
     torch.cuda.synchronize()
     if order == "local_first":
@@ -243,6 +244,25 @@ def test_two_writers_bit_exact(gpu, oracle, case, step0, order):
     assert np.array_equal(tr["counter"], want["counter"]) and np.array_equal(tr["ready"], want["ready"])
     assert tr["queue_len"] == want["queue_len"] == tp - 1 and tr["error"] == 0 and tr["gen"] == 1
     assert set(tr["queue"][:tp - 1].tolist()) == set(want["queue"][:tp - 1].tolist())
+    assert np.array_equal(fwd, oracle.release_ready(want["R"], sent, want["ready"], tp, rank))
+
+
+@pytest.mark.parametrize("step0", [False, True])
+@pytest.mark.parametrize("case", [(300, 800, 200, 4, 2, (128, 128), 3), (600, 1280, 1160, 2, 0, (256, 256), 4),
+                                  (512, 1024, 136, 2, 1, (256, 128), 2)])
+def test_split_k_bit_exact(gpu, oracle, case, step0):
+    """Sec. 7.7: split-K producer, updates per element = split degree (+ 1 for the upstream update)."""
+    M, N, K, tp, rank, tile, S = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=500 + M)
+    print(f"case={case} step0={step0}", flush=True)
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, two_writers=True, step0_store_only=step0,
+                             fwd_init=sent, split_k=S)
+    R, fwd, tr = _run_two_writers(gpu, a, b, inc, tp, rank, tile, order="concurrent", step0=step0,
+                                  split_k=S)
+    assert np.array_equal(R, want["R"])
+    assert np.array_equal(tr["counter"], want["counter"]) and np.all(tr["ready"] == 1)
+    assert tr["queue_len"] == tp - 1 and tr["error"] == 0 and tr["gen"] == 1
     assert np.array_equal(fwd, oracle.release_ready(want["R"], sent, want["ready"], tp, rank))
 
 

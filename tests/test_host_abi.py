@@ -25,8 +25,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_problem_struct_matches_header_layout():
-    # 8 int32, 5 int64, 1 uint32 (+ padding to 8), 1 int64
-    assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8 + 8
+    # 8 int32, 5 int64, 1 uint32 (+ padding to 8), 1 int64, 1 int32 (+ padding to 8)
+    assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8 + 8 + 8
+    assert t3.T3Problem.split_k.offset == 88
     assert t3.T3Problem.lda.offset == 32 and t3.T3Problem.flags.offset == 72
     assert t3.T3Problem.tile_begin.offset == 80
 
@@ -113,6 +114,11 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert L.t3_release_chunks(ctypes.byref(pw), vp(FAKE), vp(0), vp(FAKE), vp(0)) == t3.T3_ERR_NULL
     assert L.t3_rs_reduce(ctypes.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
         t3.T3_ERR_UNSUPPORTED
+    # split-K needs the atomic updates of two-writer mode and a full K-slab per part
+    assert _fused_status(t3.problem(**ok, split_k=2)) == t3.T3_ERR_UNSUPPORTED
+    assert _fused_status(t3.problem(**ok, split_k=8, flags=t3.T3_FLAG_TWO_WRITERS)) == \
+        t3.T3_ERR_UNSUPPORTED                                                       # K/64 = 4
+    assert _fused_status(t3.problem(**ok, split_k=-1)) == t3.T3_ERR_BAD_SHAPE
     # empty problems are fine and launch nothing
     assert _fused_status(t3.problem(**{**ok, "M": 0})) == t3.T3_OK
     assert _fused_status(t3.problem(**{**ok, "N": 0})) == t3.T3_OK

@@ -296,6 +296,12 @@ def test_two_writers_threshold_and_order_invariance(oracle):
     assert np.array_equal(st["R"], ref["R"])
     assert st["counter"][r] == tpc and np.all(np.delete(st["counter"], r) == 2 * tpc)
     assert np.all(st["ready"] == 1)
+    # split-K (Sec. 7.7): updates per element = split degree (+ the upstream update)
+    sk = oracle.fused_path(a, b, inc, P, r, tm, tn, two_writers=True, split_k=3)
+    assert np.array_equal(sk["R"], one["R"]) and np.all(sk["counter"] == (3 + 1) * tpc)
+    assert np.all(sk["ready"] == 1) and list(sk["updates"]) == [4] * P
+    sk0 = oracle.fused_path(a, b, inc, P, r, tm, tn, two_writers=True, split_k=3, step0_store_only=True)
+    assert sk0["counter"][r] == 3 * tpc and np.all(sk0["ready"] == 1)
     # the triggered transfers
     fwd = oracle.release_ready(two["R"], two["fwd"], two["ready"], P, r)
     assert np.array_equal(fwd, one["fwd"])
