@@ -46,7 +46,9 @@ typedef enum {
 
 typedef enum {
   T3_B_NK = 0, /* B stored N x K, K contiguous: element (k,n) at B[n*ldb + k] (forward-pass weight) */
-  T3_B_KN = 1  /* B stored K x N, N contiguous: element (k,n) at B[k*ldb + n]                       */
+  T3_B_KN = 1  /* B stored K x N, N contiguous: element (k,n) at B[k*ldb + n] (the non-transposed
+                  operand of the backward-pass GEMMs, Sec. 5.2).  K must then be a multiple of 64
+                  (T3_ERR_UNSUPPORTED otherwise) and N/tp a multiple of 8 (T3_ERR_ALIGN)            */
 } t3_b_layout;
 
 /* flags */

@@ -111,11 +111,16 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   const int64_t W = p->N / p->tp;
   if (need & kNeedAB) {
     if (p->b_layout != T3_B_NK && p->b_layout != T3_B_KN) return T3_ERR_BAD_SHAPE;
-    if (p->b_layout == T3_B_KN) return T3_ERR_UNSUPPORTED;
-    if (p->lda < p->K || p->ldb < p->K) return T3_ERR_BAD_SHAPE;
+    const bool kn = p->b_layout == T3_B_KN;
+    if (p->lda < p->K || p->ldb < (kn ? p->N : p->K)) return T3_ERR_BAD_SHAPE;
     if (p->K % 8 || p->lda % 8 || p->ldb % 8 || !aligned16(A) || !aligned16(B)) return T3_ERR_ALIGN;
+    // B stored K x N: 16-byte pieces run along N, so chunks must be cut on multiples of 8
+    // columns, and the transposed operand path takes whole K-slabs of 64 only
+    if (kn && W % 8) return T3_ERR_ALIGN;
+    if (kn && p->K % 64) return T3_ERR_UNSUPPORTED;
     // kernels address A and B with 32-bit element offsets
-    if ((int64_t)p->M * p->lda >= (1ll << 31) || (int64_t)p->N * p->ldb >= (1ll << 31))
+    if ((int64_t)p->M * p->lda >= (1ll << 31) ||
+        (int64_t)(kn ? p->K : p->N) * p->ldb >= (1ll << 31))
       return T3_ERR_UNSUPPORTED;
   }
   // kernels address R, C and a forward slot with 32-bit byte offsets
@@ -250,8 +255,8 @@ t3_status launched(void) {
 
 inline unsigned grid_size(const t3k::Plan &q) { return (unsigned)q.total_blocks; }
 
-template <int MODE>
-void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
+template <int MODE, int BKN>
+void launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
   // Persistent workgroups: as many as the chip holds at once, each walking the grid positions.
   // With release work in the grid (default release mode) every position gets a workgroup of
   // its own instead: a release position may have to wait for its chunk, and a persistent
@@ -263,13 +268,19 @@ void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
   // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
   // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.
   if (tm == 256 && tn == 256)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE>), grid, dim3(512), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE, BKN>), grid, dim3(512), 0, s, q);
   else if (tm == 256 && tn == 128)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE>), grid, dim3(512), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, BKN>), grid, dim3(512), 0, s, q);
   else if (tm == 128 && tn == 256)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE>), grid, dim3(512), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE, BKN>), grid, dim3(512), 0, s, q);
   else
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE>), grid, dim3(256), 0, s, q);
+    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE, BKN>), grid, dim3(256), 0, s, q);
+}
+
+template <int MODE>
+void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, bool b_kn, hipStream_t s) {
+  if (b_kn) launch_gemm_layout<MODE, 1>(q, tm, tn, s);
+  else launch_gemm_layout<MODE, 0>(q, tm, tn, s);
 }
 
 }  // namespace
@@ -355,7 +366,7 @@ t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, fl
                                  fwd, track, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
-  launch_gemm<t3k::kModeFused>(q, tm, tn, static_cast<hipStream_t>(stream));
+  launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN, static_cast<hipStream_t>(stream));
   return launched();
 }
 
@@ -369,7 +380,7 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
   q.R = C;   // the GEMM kernel's output pointer, addressed with ldc
-  launch_gemm<t3k::kModeGemm>(q, tm, tn, static_cast<hipStream_t>(stream));
+  launch_gemm<t3k::kModeGemm>(q, tm, tn, p->b_layout == T3_B_KN, static_cast<hipStream_t>(stream));
   return launched();
 }
 

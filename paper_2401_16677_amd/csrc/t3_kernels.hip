@@ -332,7 +332,15 @@ constexpr int kRingSlots = 4;         // 1-KiB LDS slots per wavefront for trans
 // The products are formed transposed (the B rows go in as the MFMA's first operand, the A rows
 // as its second), so that a lane ends up holding, per block, one output row and FOUR
 // CONSECUTIVE COLUMNS: the incoming partial is read and the sum written with 16-byte accesses.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE>
+//
+// BKN = 1: B is stored K x N with N contiguous (the layout of the backward-pass GEMMs).  Its
+// stage region then holds 64 k-rows of BN values; the MFMA operand (8 consecutive k for one n
+// per lane) is fetched with the transposing LDS read ds_read_b64_tr_b16: in each block of 16
+// lanes, lane i supplies the address of 4 consecutive n of k-row i / 4 (n offset 4 (i % 4)) and
+// receives, for n = i, the values of the block's 4 k-rows.  32-byte pieces of a k-row sit at
+// position (piece ^ sw(k)), sw(k) = (k & 3) | ((k >> 3) & 1) << 2, which spreads the 8 k-rows
+// that 32 lanes read together over all banks.  K must be a multiple of 64 in this layout.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE, int BKN>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2)))
 void gemm_tile_kernel(const Plan p) {
   constexpr int NW = WAVES_M * WAVES_N;
@@ -382,7 +390,8 @@ void gemm_tile_kernel(const Plan p) {
   const int part_slabs = (p.K / kBK) / p.split_k;
   const int k0 = part * part_slabs * kBK;
   const int Kpart = (part == p.split_k - 1) ? p.K - k0 : part_slabs * kBK;
-  const char *const Ap = (const char *)p.A + (int64_t)k0 * 2, *const Bp = (const char *)p.B + (int64_t)k0 * 2;
+  const char *const Ap = (const char *)p.A + (int64_t)k0 * 2;
+  const char *const Bp = (const char *)p.B + (BKN ? (int64_t)k0 * p.ldb * 2 : (int64_t)k0 * 2);
   Tile tl;
   int slot = 0, agent = 0;
   const int role = decode_block(p, blk, tl, slot, agent);
@@ -414,10 +423,23 @@ void gemm_tile_kernel(const Plan p) {
     const int r = wave * (BM / NW) + q * kRPC + cp_row;
     offA[q] = (uint32_t)((min(m0 + r, p.M - 1) * p.lda + chunk_of(BM / NW, q) * 8) * 2);
   }
+  constexpr int kBRowBytes = BN * 2;             // (BKN) one k-row of the B region
+  constexpr int kSwMask = (BN / 16 < 8 ? BN / 16 : 8) - 1;
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
-    const int r = wave * (BN / NW) + q * kRPC + cp_row;
-    offB[q] = (uint32_t)((min(n0 + r, col_hi - 1) * p.ldb + chunk_of(BN / NW, q) * 8) * 2);
+    if (BKN) {
+      // copy (wave * NB + q) fills bytes [1024 (wave NB + q), +1024) of the B region: lane l
+      // lands in k-row L / kBRowBytes at 16-byte position cp, which holds half (cp & 1) of
+      // 32-byte piece (cp >> 1) ^ sw(k)
+      const int L = (wave * NB + q) * 1024 + lane * 16;
+      const int k = L / kBRowBytes, cp = (L % kBRowBytes) / 16;
+      const int sw = ((k & 3) | (((k >> 3) & 1) << 2)) & kSwMask;
+      const int ncol = (((cp >> 1) ^ sw) * 2 + (cp & 1)) * 8;
+      offB[q] = (uint32_t)((k * p.ldb + min(n0 + ncol, col_hi - 8)) * 2);
+    } else {
+      const int r = wave * (BN / NW) + q * kRPC + cp_row;
+      offB[q] = (uint32_t)((min(n0 + r, col_hi - 1) * p.ldb + chunk_of(BN / NW, q) * 8) * 2);
+    }
   }
   const int ldsA_w = wave * (BM / NW) * kRowBytes;            // this wavefront's rows, stage 0
   const int ldsB_w = kBOff + wave * (BN / NW) * kRowBytes;
@@ -430,7 +452,7 @@ void gemm_tile_kernel(const Plan p) {
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
   auto issue_copies = [&](int kt, int stage, int q0, int q1) {
     const char *a = Ap + (int64_t)kt * (kBK * 2);
-    const char *b = Bp + (int64_t)kt * (kBK * 2);
+    const char *b = Bp + (BKN ? (int64_t)kt * kBK * p.ldb * 2 : (int64_t)kt * (kBK * 2));
     const uint32_t dst = lds_base + stage * kStageBytes;
 #pragma unroll
     for (int q = 0; q < NA; ++q)
@@ -459,6 +481,11 @@ void gemm_tile_kernel(const Plan p) {
     fragA[kk] = (wm * WM + fr) * kRowBytes + pos;
     fragB[kk] = kBOff + (wn * WN + fr) * kRowBytes + pos;
   }
+  // (BKN) this lane's address parts of the transposing reads: k-row 8 (lane >> 4) + (fr >> 2) of
+  // a k-step's 32 (+ 4 for the second read), 8 bytes at n offset 4 (fr & 3) of 32-byte piece
+  // (wn WN / 16 + j) ^ sw
+  const int trB = kBOff + (8 * fq + (fr >> 2)) * kBRowBytes + (fr & 3) * 8;
+  const int trSw = ((fr >> 2) | ((fq & 1) << 2)) & kSwMask;
 
   const int nkf = Kpart / kBK;                   // full slabs
   const int ktail = Kpart - nkf * kBK;           // leftover elements of K (a multiple of 8)
@@ -561,8 +588,20 @@ void gemm_tile_kernel(const Plan p) {
       fa[u & 1][i] = *(const bf16x8 *)(lds + stage_off + fragA[kk] + (h * FMH + i) * 16 * kRowBytes);
     if (h == 0) {
 #pragma unroll
-      for (int j = 0; j < FN; ++j)
-        fb[kk & 1][j] = *(const bf16x8 *)(lds + stage_off + fragB[kk] + j * 16 * kRowBytes);
+      for (int j = 0; j < FN; ++j) {
+        if (BKN) {
+          typedef __attribute__((ext_vector_type(4))) short s16x4;
+          typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+          const char *a0 = lds + stage_off + trB + 32 * kk * kBRowBytes + (((wn * (WN / 16) + j) ^ trSw) << 5);
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_void_ptr)a0);
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_void_ptr)(a0 + 4 * kBRowBytes));
+          typedef __attribute__((ext_vector_type(8))) short s16x8;
+          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          fb[kk & 1][j] = __builtin_bit_cast(bf16x8, both);
+        } else {
+          fb[kk & 1][j] = *(const bf16x8 *)(lds + stage_off + fragB[kk] + j * 16 * kRowBytes);
+        }
+      }
     }
   };
   auto mfma_u = [&](int u) {
@@ -608,13 +647,13 @@ void gemm_tile_kernel(const Plan p) {
         issue_copies(kt_next, st_next, u * NL / MH, (u + 1) * NL / MH);
         mfma_u((u + US - 1) % US);                 // u == 0: last micro-step of slab kt-1
       }
-      sched_kstep<MH, FMH, FN, 0>();
+      sched_kstep<MH, FMH, FN, BKN ? FN : 0>();   // (the transposing reads are two per column block)
 #pragma unroll
       for (int u = MH; u < US; ++u) {              // k-step 1
         read_u(u, so);
         mfma_u(u - 1);
       }
-      sched_kstep<MH, FMH, FN, 0>();
+      sched_kstep<MH, FMH, FN, BKN ? FN : 0>();   // (the transposing reads are two per column block)
       stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     }
     mfma_u(US - 1);
@@ -636,6 +675,7 @@ void gemm_tile_kernel(const Plan p) {
     }
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
+      if (BKN) break;                              // (no ragged K in this layout)
       uint4 v = zero;
       if (chunk_of(BN / NW, q) * 8 < ktail) v = *(const uint4 *)(Bp + kb + offB[q]);
       *(uint4 *)(lds + ldsB_w + q * 1024 + lane * 16) = v;

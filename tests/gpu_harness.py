@@ -13,7 +13,7 @@ def to_dev_bits(bits):
 
 
 def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfused=False,
-            ldr_pad=0, lda_pad=0, tile_begin=0):
+            ldr_pad=0, lda_pad=0, tile_begin=0, b_kn=False):
     """One call of the fused path (or the unfused GEMM-then-reduce pair).  Returns a dict
     with R, fwd, counter, ready, queue, queue_len (numpy) and, for unfused, C."""
     M, K = a_bits.shape
@@ -27,6 +27,11 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
         b_host[:, :K] = b_bits
     else:
         a_host, b_host = a_bits, b_bits
+    ldb = K + lda_pad
+    if b_kn:                       # the same B, stored K x N (N contiguous), rows padded by lda_pad
+        ldb = N + lda_pad
+        b_host = np.zeros((K, ldb), dtype=np.uint16)
+        b_host[:, :N] = np.ascontiguousarray(b_bits.T)
     A, B = to_dev_bits(a_host), to_dev_bits(b_host)
     ldr = N + ldr_pad
     R = torch.full((max(M, 1), ldr), 123.0, dtype=torch.float32, device=dev)
@@ -35,7 +40,8 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
     fwd = torch.full((max(tp - 1, 1), max(M, 1), max(W, 1)), SENTINEL, dtype=torch.float32,
                      device=dev)
     track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
-    p = t3.problem(M, N, K, tp, rank, tile[0], tile[1], lda=K + lda_pad, ldb=K + lda_pad,
+    p = t3.problem(M, N, K, tp, rank, tile[0], tile[1], lda=K + lda_pad, ldb=ldb,
+                   b_layout=t3.T3_B_KN if b_kn else t3.T3_B_NK,
                    ldr=ldr, ldc=N, tile_limit=tile_limit, flags=flags, tile_begin=tile_begin)
     t3.t3_track_reset(tp, track)
     out = {}

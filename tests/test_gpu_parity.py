@@ -77,6 +77,38 @@ def test_integer_inputs_bit_exact(gpu, oracle, case, step0, direct):
     _check_ints(got, want, tp, want["own"])
 
 
+KN_CASES = [
+    # M,   N,    K,   tp, rank, tile          (K a multiple of 64, W a multiple of 8)
+    (256, 1024, 256, 4, 0, (128, 128)),
+    (300, 832, 192, 4, 2, (128, 128)),
+    (520, 1072, 128, 2, 1, (256, 128)),
+    (260, 1200, 320, 3, 0, (128, 256)),
+    (600, 1296, 1216, 2, 0, (256, 256)),
+    (512, 2048, 64, 4, 3, (256, 256)),
+]
+
+
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("case", KN_CASES)
+def test_b_stored_k_by_n_bit_exact(gpu, oracle, case, unfused, direct):
+    """B stored K x N, N contiguous (the backward-pass GEMMs' layout): same results as with the
+    N x K storage, every tile shape, ragged M and W, padded leading dimensions."""
+    M, N, K, tp, rank, tile = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=700 + M)
+    print(f"case={case} unfused={unfused} direct={direct}", flush=True)
+    want = oracle.fused_path(a, np.ascontiguousarray(b.T), inc, tp, rank, *tile, b_layout=oracle.B_KN,
+                             fwd_direct=direct,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=_flags(False, direct), unfused=unfused,
+                      lda_pad=8, b_kn=True)
+    assert np.array_equal(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"])
+    _check_ints(got, want, tp, want["own"])
+    if unfused:
+        assert np.array_equal(got["C"], oracle.gemm_rows(a, b).astype(np.float32))
+
+
 @pytest.mark.parametrize("direct", [False, True])
 @pytest.mark.parametrize("case", EXACT_CASES[:4])
 def test_unfused_baseline_bit_exact(gpu, oracle, case, direct):
@@ -455,6 +487,37 @@ def test_paper_table2_shapes_sampled_rows(gpu, oracle, name):
     print(f"max normwise error over chunks {max(errs):.3e}", flush=True)
     assert max(errs) <= EXPECT
     assert not bool((fwd == gpu.SENTINEL).all(dim=2).any())
+
+
+def test_full_size_b_stored_k_by_n(gpu, oracle):
+    """gpt3_outproj at full size with B stored K x N, direct release: sampled rows."""
+    import torch
+    w = wl.WORKLOADS["gpt3_outproj"]
+    a, b, inc = wl.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 1)
+    rows = np.array(sorted({0, w.M - 1} | set(rng.integers(0, w.M, 16).tolist())), dtype=np.int32)
+    S = oracle.reduce_rows(oracle.gemm_rows(a, b, rows=rows), inc, w.tp, rows=rows)
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(np.ascontiguousarray(b.T))
+    R = torch.from_numpy(inc).to(dev)
+    fwd = torch.full((w.tp - 1, w.M, w.W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(w.tp), dtype=torch.int32, device=dev)
+    p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n, b_layout=t3.T3_B_KN,
+                   flags=t3.T3_FLAG_FWD_DIRECT)
+    t3.t3_track_reset(w.tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+    order, own = oracle.chunk_order(w.tp, w.rank)
+    tr = t3.read_track(track, w.tp)
+    assert np.all(tr["ready"] == 1) and tr["queue_len"] == w.tp - 1 and tr["error"] == 0
+    idx = torch.from_numpy(rows.astype(np.int64)).to(dev)
+    Rg = R.index_select(0, idx).cpu().numpy()
+    fg = fwd.index_select(1, idx).cpu().numpy()
+    W = w.W
+    errs = [gpu.rel_err(Rg[:, c * W:(c + 1) * W] if c == own else fg[s], S[:, c * W:(c + 1) * W])
+            for s, c in enumerate(int(x) for x in order)]
+    print(f"max normwise error over chunks {max(errs):.3e}", flush=True)
+    assert max(errs) <= EXPECT
 
 
 def test_graph_replays_match_eager(gpu, oracle):

@@ -94,7 +94,10 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert _fused_status(t3.problem(**ok), A=FAKE + 2) == t3.T3_ERR_ALIGN
     assert _fused_status(t3.problem(**ok), R=FAKE + 4) == t3.T3_ERR_ALIGN
     assert _fused_status(t3.problem(**{**ok, "N": 1016})) == t3.T3_ERR_ALIGN   # W = 254
-    assert _fused_status(t3.problem(**ok, b_layout=t3.T3_B_KN)) == t3.T3_ERR_UNSUPPORTED
+    # B stored K x N: whole K-slabs of 64 only, chunks cut on multiples of 8 columns, ldb >= N
+    assert _fused_status(t3.problem(**{**ok, "K": 200}, b_layout=t3.T3_B_KN)) == t3.T3_ERR_UNSUPPORTED
+    assert _fused_status(t3.problem(**{**ok, "N": 1008}, b_layout=t3.T3_B_KN)) == t3.T3_ERR_ALIGN  # W = 252
+    assert _fused_status(t3.problem(**ok, b_layout=t3.T3_B_KN, ldb=512)) == t3.T3_ERR_BAD_SHAPE
     assert _fused_status(t3.problem(**ok, flags=8)) == t3.T3_ERR_UNSUPPORTED
     assert _fused_status(t3.problem(**ok, b_layout=7)) == t3.T3_ERR_BAD_SHAPE
     # R of 4 GiB or more (32-bit byte offsets in the kernels): refused, nothing launched
