@@ -725,17 +725,27 @@ void gemm_tile_kernel(const Plan p) {
     *(f32x4 *)(slot + u_acc[1]) = acc[i][2 * jj + 1];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane * 16);
-      if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi)) {
-        const uint32_t blk_off = ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u;
-        if (two_writers) {       // op-and-store (Sec. 4.3): the other writer adds into the same words
-          float *dst = (float *)((char *)const_cast<float *>(out_base) + blk_off + out_u[h]);
+      const uint32_t blk_off = ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u;
+      if (two_writers) {
+        // op-and-store (Sec. 4.3): the other writer adds into the same words.  One word per lane
+        // and instruction, so that an instruction covers two whole 128-byte rows of the pair.
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            __hip_atomic_fetch_add(dst + e, v[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-          store_agent(out_rsrc, out_u[h], blk_off, v);
+        for (int e = 0; e < 4; ++e) {
+          const int rp = 2 * e + (lane_e >> 5);            // row position in the slot (see pair_lane)
+          const int r = h ? (rp ^ 1) : rp;                 // the row it holds ...
+          const int ar = 8 * h + r;
+          const int ac = 4 * (((lane_e & 31) >> 2) ^ r) + (lane_e & 3);   // ... and the column
+          const float v = *(const float *)(slot + h * 1024 + e * 256 + lane_e * 4);
+          if (full || (rw0 + 16 * i + ar < p.M && cw0 + 32 * jj + ac < col_hi)) {
+            float *dst = (float *)((char *)const_cast<float *>(out_base) + blk_off) +
+                         (int64_t)(rw0 + ar) * ld_out + (cw0 - col_org + ac);
+            __hip_atomic_fetch_add(dst, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
         }
+      } else {
+        const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane * 16);
+        if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
+          store_agent(out_rsrc, out_u[h], blk_off, v);
       }
     }
     // keep the scheduler from running many pairs ahead: it would park their values in registers
@@ -803,16 +813,15 @@ __global__ __launch_bounds__(kThreads) void upstream_update_kernel(const Plan p)
   const int col_lo = tl.c * p.W;
   const int n0 = col_lo + tl.nj * BN;
   const int rows = min(BM, p.M - m0);
-  const int cols4 = min(BN, col_lo + p.W - n0) >> 2;
-  const int total = rows * cols4;
+  const int cols = min(BN, col_lo + p.W - n0);
+  const int total = rows * cols;
+  // one word per lane: an atomic instruction then covers whole 128-byte lines
   for (int e = threadIdx.x; e < total; e += kThreads) {
-    const int rr = e / cols4, cc = e - rr * cols4;
+    const int rr = e / cols, cc = e - rr * cols;
     const int64_t row = m0 + rr;
-    const f32x4 v = __builtin_nontemporal_load((const f32x4 *)(p.C + row * p.ldc + n0) + cc);
-    float *dst = p.R + row * p.ldr + n0 + 4 * cc;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      __hip_atomic_fetch_add(dst + q, v[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float v = __builtin_nontemporal_load(p.C + row * p.ldc + n0 + cc);
+    __hip_atomic_fetch_add(p.R + row * p.ldr + n0 + cc, v, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
   }
   track_tile(p, trk, tl.c);
 }
