@@ -185,6 +185,33 @@ def main():
         unfused_step()
     t_unfused = timed(unfused_step, args.steps)
 
+    # The other release mode, fused and unfused, timed the same way (reported beside the main
+    # figures: `copy` is the literal add-in-place-then-release path, `direct` writes forwarded
+    # sums straight to their forward slots).
+    o_flags = 0 if args.direct else t3.T3_FLAG_FWD_DIRECT
+    po = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n, flags=o_flags)
+
+    def o_fused():
+        t3.t3_gemm_rs_fused(po, A, B, R, fwd, track)
+
+    def o_unfused():
+        t3.t3_gemm(po, A, B, C)
+        t3.t3_rs_reduce(po, C, R, fwd, track)
+
+    other = {}
+    for key, step in (("ms_per_step", o_fused), ("unfused_ms_per_step", o_unfused)):
+        R.copy_(inc_dev)
+        t_end = time.perf_counter() + 0.2
+        while time.perf_counter() < t_end:
+            for _ in range(20):
+                step()
+            torch.cuda.synchronize()
+        other[key] = timed(step, args.steps) * 1e3
+    other["tflops"] = w.flop / (other["ms_per_step"] * 1e-3) / 1e12
+    other["speedup_vs_unfused"] = other["unfused_ms_per_step"] / other["ms_per_step"]
+    tr = t3.read_track(track, w.tp)
+    assert tr["error"] == 0, "tracker error in the other release mode"
+
     tflops = w.flop / t_fused / 1e12
     bytes_alg = algorithmic_bytes(w, args.direct)
     t_mfma = w.flop / (PEAK_BF16_TFLOPS * 1e12)
@@ -216,6 +243,7 @@ def main():
         "unfused_ms_per_step": t_unfused * 1e3,
         "speedup_vs_unfused": t_unfused / t_fused,
         "roofline": roof,
+        ("release_copy" if args.direct else "release_direct"): other,
     }
     if not args.no_cpu:
         out["cpu_baseline"], _, _ = cpu_baseline(w, a_bits, b_bits, inc)

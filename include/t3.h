@@ -88,6 +88,12 @@ typedef struct {
                              S <= 64): S workgroups share a tile, each multiplying a part of K and
                              adding it into R, so the local GEMM makes S updates per element and
                              a chunk's threshold is (S + 1) * tpc (Sec. 7.7)                        */
+  int32_t upstream_agents; /* t3_upstream_update only.  0: one workgroup per tile.  n > 0: at most n
+                             workgroups walk the tiles in issue order, which caps the memory
+                             traffic the upstream writer has in flight beside the GEMM: the
+                             software stand-in for the arbitration policy of Sec. 4.5, which holds
+                             communication accesses back while the producer is memory-bound.
+                             < 0 is T3_ERR_BAD_SHAPE                                                */
 } t3_problem;
 
 /*

@@ -32,7 +32,8 @@ class T3Problem(ctypes.Structure):
                 ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64),
                 ("ldr", ctypes.c_int64), ("ldc", ctypes.c_int64),
                 ("tile_limit", ctypes.c_int64), ("flags", ctypes.c_uint32),
-                ("tile_begin", ctypes.c_int64), ("split_k", ctypes.c_int32)]
+                ("tile_begin", ctypes.c_int64), ("split_k", ctypes.c_int32),
+                ("upstream_agents", ctypes.c_int32)]
 
 
 class T3Error(RuntimeError):
@@ -91,12 +92,13 @@ def _check(status, what):
 
 
 def problem(M, N, K, tp, rank, tile_m=0, tile_n=0, b_layout=T3_B_NK, lda=None, ldb=None,
-            ldr=None, ldc=None, tile_limit=-1, flags=0, tile_begin=0, split_k=0):
+            ldr=None, ldc=None, tile_limit=-1, flags=0, tile_begin=0, split_k=0,
+            upstream_agents=0):
     return T3Problem(M, N, K, tp, rank, tile_m, tile_n, b_layout,
                      K if lda is None else lda,
                      (K if b_layout == T3_B_NK else N) if ldb is None else ldb,
                      N if ldr is None else ldr, N if ldc is None else ldc, tile_limit, flags,
-                     tile_begin, split_k)
+                     tile_begin, split_k, upstream_agents)
 
 
 def _dptr(t):

@@ -415,7 +415,11 @@ t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *
                                  incoming, R, nullptr, track, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
-  const dim3 grid(grid_size(q)), block(t3k::kThreads);
+  if (p->upstream_agents < 0) return T3_ERR_BAD_SHAPE;
+  unsigned blocks = grid_size(q);
+  if (p->upstream_agents > 0 && (unsigned)p->upstream_agents < blocks)
+    blocks = (unsigned)p->upstream_agents;     // the rest of the positions are walked in a loop
+  const dim3 grid(blocks), block(t3k::kThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (tm == 256 && tn == 256)
     hipLaunchKernelGGL((t3k::upstream_update_kernel<256, 256>), grid, block, 0, s, q);

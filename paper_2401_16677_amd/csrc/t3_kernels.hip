@@ -804,26 +804,42 @@ __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
 // the first chunk stored only (Sec. 4.4) it has no upstream update: those tiles are skipped.
 template <int BM, int BN>
 __global__ __launch_bounds__(kThreads) void upstream_update_kernel(const Plan p) {
-  Tile tl;
-  int slot = 0, agent = 0;
-  if (decode_block(p, blockIdx.x, tl, slot, agent) != kRoleTile) return;
-  if ((p.flags & kFlagStep0StoreOnly) && tl.s == 0) return;
   const Trk trk = trk_open(p);
-  const int m0 = tl.mi * BM;
-  const int col_lo = tl.c * p.W;
-  const int n0 = col_lo + tl.nj * BN;
-  const int rows = min(BM, p.M - m0);
-  const int cols = min(BN, col_lo + p.W - n0);
-  const int total = rows * cols;
-  // one word per lane: an atomic instruction then covers whole 128-byte lines
-  for (int e = threadIdx.x; e < total; e += kThreads) {
-    const int rr = e / cols, cc = e - rr * cols;
-    const int64_t row = m0 + rr;
-    const float v = __builtin_nontemporal_load(p.C + row * p.ldc + n0 + cc);
-    __hip_atomic_fetch_add(p.R + row * p.ldr + n0 + cc, v, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+  // one workgroup per grid position, or fewer workgroups walking the positions in issue order
+  for (int pos = blockIdx.x; pos < p.total_blocks; pos += gridDim.x) {
+    Tile tl;
+    int slot = 0, agent = 0;
+    if (decode_block(p, pos, tl, slot, agent) != kRoleTile) continue;
+    if ((p.flags & kFlagStep0StoreOnly) && tl.s == 0) continue;
+    const int m0 = tl.mi * BM;
+    const int col_lo = tl.c * p.W;
+    const int n0 = col_lo + tl.nj * BN;
+    const int rows = min(BM, p.M - m0);
+    const int cols = min(BN, col_lo + p.W - n0);
+    const int total = rows * cols;
+    // One word per lane, so that an atomic instruction covers whole 128-byte lines; eight loads
+    // in flight per lane before their adds go out (a workgroup would otherwise move one word per
+    // lane per memory round trip).
+    constexpr int kBatch = 8;
+    for (int e0 = threadIdx.x; e0 < total; e0 += kBatch * kThreads) {
+      float v[kBatch];
+      int64_t at[kBatch];
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const int e = e0 + k * kThreads;
+        const int rr = e / cols, cc = e - rr * cols;
+        at[k] = (int64_t)(m0 + rr);
+        v[k] = 0.f;
+        if (e < total) v[k] = __builtin_nontemporal_load(p.C + at[k] * p.ldc + n0 + cc);
+        at[k] = at[k] * p.ldr + n0 + cc;
+      }
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k)
+        if (e0 + k * kThreads < total)
+          __hip_atomic_fetch_add(p.R + at[k], v[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    track_tile(p, trk, tl.c);
   }
-  track_tile(p, trk, tl.c);
 }
 
 // The triggered transfers, as a launch of their own (two-writer mode, where no launch can wait

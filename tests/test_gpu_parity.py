@@ -221,7 +221,7 @@ def test_ring_of_virtual_ranks_closes_on_unsliced_gemm(gpu, oracle, kind):
 
 
 def _run_two_writers(gpu, a, b, inc, tp, rank, tile, *, order, step0=False, tile_begin=0, tile_limit=-1,
-                     split_k=0):
+                     split_k=0, upstream_agents=0):
     """Two-writer mode through the C ABI: the fused call and the upstream update, one after the
     other in either order or on two streams at once, then the triggered transfers."""
     import torch
@@ -236,7 +236,7 @@ def _run_two_writers(gpu, a, b, inc, tp, rank, tile, *, order, step0=False, tile
     track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
     flags = t3.T3_FLAG_TWO_WRITERS | (t3.T3_FLAG_STEP0_STORE_ONLY if step0 else 0)
     p = t3.problem(M, N, K, tp, rank, *tile, ldc=N, flags=flags, tile_begin=tile_begin,
-                   tile_limit=tile_limit, split_k=split_k)
+                   tile_limit=tile_limit, split_k=split_k, upstream_agents=upstream_agents)
     t3.t3_track_reset(tp, track)
     torch.cuda.synchronize()
     if order == "local_first":
@@ -276,6 +276,24 @@ def test_two_writers_bit_exact(gpu, oracle, case, step0, order):
     assert np.array_equal(tr["counter"], want["counter"]) and np.array_equal(tr["ready"], want["ready"])
     assert tr["queue_len"] == want["queue_len"] == tp - 1 and tr["error"] == 0 and tr["gen"] == 1
     assert set(tr["queue"][:tp - 1].tolist()) == set(want["queue"][:tp - 1].tolist())
+    assert np.array_equal(fwd, oracle.release_ready(want["R"], sent, want["ready"], tp, rank))
+
+
+@pytest.mark.parametrize("agents", [1, 3, 1000])
+@pytest.mark.parametrize("case", [(300, 800, 200, 4, 2, (128, 128)), (1024, 4096, 512, 4, 1, (256, 256))])
+def test_two_writers_throttled_upstream_bit_exact(gpu, oracle, case, agents):
+    """The upstream writer held to a few workgroups that walk the tiles (the software stand-in for
+    the arbitration of Sec. 4.5) changes when its updates land, not what is computed."""
+    M, N, K, tp, rank, tile = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=700 + M)
+    print(f"case={case} agents={agents}", flush=True)
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, two_writers=True, fwd_init=sent)
+    R, fwd, tr = _run_two_writers(gpu, a, b, inc, tp, rank, tile, order="concurrent",
+                                  upstream_agents=agents)
+    assert np.array_equal(R, want["R"])
+    assert np.array_equal(tr["counter"], want["counter"]) and np.all(tr["ready"] == 1)
+    assert tr["queue_len"] == tp - 1 and tr["error"] == 0 and tr["gen"] == 1
     assert np.array_equal(fwd, oracle.release_ready(want["R"], sent, want["ready"], tp, rank))
 
 

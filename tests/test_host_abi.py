@@ -25,9 +25,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_problem_struct_matches_header_layout():
-    # 8 int32, 5 int64, 1 uint32 (+ padding to 8), 1 int64, 1 int32 (+ padding to 8)
+    # 8 int32, 5 int64, 1 uint32 (+ padding to 8), 1 int64, 2 int32
     assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8 + 8 + 8
-    assert t3.T3Problem.split_k.offset == 88
+    assert t3.T3Problem.split_k.offset == 88 and t3.T3Problem.upstream_agents.offset == 92
     assert t3.T3Problem.lda.offset == 32 and t3.T3Problem.flags.offset == 72
     assert t3.T3Problem.tile_begin.offset == 80
 
@@ -115,6 +115,10 @@ def test_bad_arguments_are_refused_before_any_launch():
     pw = t3.problem(**ok, flags=t3.T3_FLAG_TWO_WRITERS)
     assert L.t3_upstream_update(ctypes.byref(pw), vp(0), vp(FAKE), vp(FAKE), vp(0)) == t3.T3_ERR_NULL
     assert L.t3_release_chunks(ctypes.byref(pw), vp(FAKE), vp(0), vp(FAKE), vp(0)) == t3.T3_ERR_NULL
+    pw = t3.problem(**ok, flags=t3.T3_FLAG_TWO_WRITERS, upstream_agents=-1)
+    assert L.t3_upstream_update(ctypes.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
+        t3.T3_ERR_BAD_SHAPE
+    pw = t3.problem(**ok, flags=t3.T3_FLAG_TWO_WRITERS)
     assert L.t3_rs_reduce(ctypes.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
         t3.T3_ERR_UNSUPPORTED
     # split-K needs the atomic updates of two-writer mode and a full K-slab per part
