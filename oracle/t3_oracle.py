@@ -159,9 +159,36 @@ def executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin=0):
     return mask, L, B0
 
 
+def to_bf16_bits(x):
+    """fp32 -> bfloat16 bit patterns (uint16), round to nearest, ties to even: the 16-bit
+    format activations travel in under mixed precision (Sec. 5.2).  bfloat16 is the upper half
+    of an fp32 word, so rounding adds half an ulp of the kept part (less one when the kept part
+    is even) and truncates.  A NaN gives a quiet NaN of the same sign."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    kept_is_odd = (u >> np.uint64(16)) & np.uint64(1)
+    rounded = (u + np.uint64(0x7FFF) + kept_is_odd) >> np.uint64(16)
+    is_nan = (u & np.uint64(0x7FFFFFFF)) > np.uint64(0x7F800000)
+    quiet = ((u >> np.uint64(16)) & np.uint64(0x8000)) | np.uint64(0x7FC0)
+    return np.where(is_nan, quiet, rounded).astype(np.uint16)
+
+
+def from_bf16_bits(b):
+    """bfloat16 bit patterns -> the fp32 values they denote (exact)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _new_fwd(P, M, W, fwd_init, fwd_bf16):
+    dt = np.uint16 if fwd_bf16 else np.float32
+    if fwd_init is None:
+        return np.zeros((max(P - 1, 0), M, W), dtype=dt)
+    if np.asarray(fwd_init).dtype != dt:
+        raise ValueError("fwd_init must be %s" % np.dtype(dt).name)
+    return np.array(fwd_init, dtype=dt, copy=True)
+
+
 def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
                tile_limit=-1, tile_begin=0, step0_store_only=False, fwd_direct=False,
-               fwd_init=None, two_writers=False, R_init=None, split_k=1):
+               fwd_init=None, two_writers=False, R_init=None, split_k=1, fwd_bf16=False):
     """The whole path for one rank, by the definition.
 
     Returns a dict with
@@ -172,6 +199,8 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
     Default release mode: every executed tile is added in place into R and a chunk
     is copied to its forward slot once complete.  fwd_direct: sums of forwarded
     chunks go straight to the forward slot and R keeps the incoming data there.
+    fwd_bf16: the forward slots hold bfloat16 bit patterns (uint16; fwd_init likewise): what
+    is written there is the fp32 sum rounded by to_bf16_bits; R stays fp32.
     Only the tiles [tile_begin, tile_limit) of the issue order are executed (a ring step s is
     the range [s*tpc, (s+1)*tpc), Sec. 4.1); elements outside executed tiles keep their
     initial contents, and a chunk is complete only if all of its tiles were executed.
@@ -187,11 +216,11 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
     mask, L, B0 = executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin)
     if two_writers:
         return _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0,
-                            order, own, step0_store_only, fwd_init, R_init, split_k)
+                            order, own, step0_store_only, fwd_init, R_init, split_k, fwd_bf16)
     trk = track(M, N, P, r, tile_m, tile_n, np.arange(B0, L, dtype=np.int64))
 
-    fwd = (np.zeros((max(P - 1, 0), M, W), dtype=np.float32) if fwd_init is None
-           else np.array(fwd_init, dtype=np.float32, copy=True))
+    fwd = _new_fwd(P, M, W, fwd_init, fwd_bf16)
+    sent = to_bf16_bits if fwd_bf16 else (lambda x: x)      # what a forward slot receives
     R = incoming.copy()
     for s in range(P):
         c = int(order[s])
@@ -200,9 +229,9 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
             R[:, cols] = np.where(mask[:, cols], S[:, cols], incoming[:, cols])
         if c != own:
             if fwd_direct:
-                fwd[s] = np.where(mask[:, cols], S[:, cols], fwd[s])
+                fwd[s] = np.where(mask[:, cols], sent(S[:, cols]), fwd[s])
             elif trk["ready"][c]:
-                fwd[s] = S[:, cols]
+                fwd[s] = sent(S[:, cols])
     out = dict(trk)
     out.update(R=R, fwd=fwd, owned=R[:, own * W:(own + 1) * W].copy(), order=order, own=own,
                tiles_per_chunk=tiles_per_chunk(M, N, P, tile_m, tile_n), executed=L - B0)
@@ -210,7 +239,7 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
 
 
 def _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0, order, own,
-                 step0_store_only, fwd_init, R_init, split_k=1):
+                 step0_store_only, fwd_init, R_init, split_k=1, fwd_bf16=False):
     """Both writers add into R over the tiles [B0, L).  R_init must be zero on executed tiles:
     then 0 + x is exact and the second add rounds once, whichever writer comes first, so the
     result is S = fl32(incoming + C) either way (the sums of reduce_rows)."""
@@ -233,22 +262,23 @@ def _two_writers(A_bits, B_bits, incoming, P, r, tile_m, tile_n, S, mask, L, B0,
     else:
         landed += list(range(B0, L))
     trk = track(M, N, P, r, tile_m, tile_n, np.array(landed, dtype=np.int64), updates=upd)
-    fwd = (np.zeros((max(P - 1, 0), M, W), dtype=np.float32) if fwd_init is None
-           else np.array(fwd_init, dtype=np.float32, copy=True))
+    fwd = _new_fwd(P, M, W, fwd_init, fwd_bf16)
     out = dict(trk)
     out.update(R=R, fwd=fwd, owned=R[:, own * W:(own + 1) * W].copy(), order=order, own=own,
                tiles_per_chunk=tpc, executed=L - B0, updates=upd)
     return out
 
 
-def release_ready(R, fwd, ready, P, r):
+def release_ready(R, fwd, ready, P, r, fwd_bf16=False):
     """The triggered transfers (Sec. 4.2.2): every forwarded chunk whose ready flag is set is
-    copied from R into its forward slot.  Returns the new fwd."""
+    copied from R into its forward slot (rounded to bfloat16 bit patterns if fwd_bf16).
+    Returns the new fwd."""
     order, own = chunk_order(P, r)
     W = R.shape[1] // P
-    fwd = np.array(fwd, dtype=np.float32, copy=True)
+    fwd = _new_fwd(P, R.shape[0], W, fwd, fwd_bf16)
     for s in range(P - 1):
         c = int(order[s])
         if ready[c]:
-            fwd[s] = R[:, c * W:(c + 1) * W]
+            chunk = R[:, c * W:(c + 1) * W]
+            fwd[s] = to_bf16_bits(chunk) if fwd_bf16 else chunk
     return fwd

@@ -400,3 +400,75 @@ def test_rejects_bad_arguments(oracle):
         oracle.reduce_rows(np.zeros((2, 6)), np.zeros((2, 6), np.float32), 4)
     with pytest.raises(ValueError):
         oracle.track(8, 8, 2, 0, 4, 4, np.array([99]))
+
+
+# ---------------------------------------------------------------- bfloat16 forward slots (Sec. 5.2)
+
+def test_bf16_rounding_against_library_and_closed_forms(oracle):
+    import torch
+    rng = np.random.default_rng(5)
+    # random bit patterns over the whole fp32 range (NaNs taken out), plus every kind of edge
+    u = rng.integers(0, 2 ** 32, size=200000, dtype=np.uint64).astype(np.uint32)
+    u = u[(u & 0x7FFFFFFF) <= 0x7F800000]
+    edge = np.array([0x00000000, 0x80000000, 0x00000001, 0x00008000, 0x00018000, 0x7F7FFFFF,
+                     0xFF7FFFFF, 0x7F800000, 0xFF800000, 0x3F800000, 0x3F808000, 0x3F818000,
+                     0x3F807FFF, 0x3F808001, 0x3F817FFF, 0x3F818001], dtype=np.uint32)
+    u = np.concatenate([u, edge])
+    x = u.view(np.float32)
+    got = oracle.to_bf16_bits(x)
+    lib = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, lib)                      # the library's fp32 -> bf16 conversion
+    # closed forms: a tie goes to the even neighbour, anything past it goes up, below it down
+    def one(bits):
+        return int(oracle.to_bf16_bits(np.array([bits], dtype=np.uint32).view(np.float32))[0])
+    assert one(0x3F808000) == 0x3F80 and one(0x3F818000) == 0x3F82       # ties: down / up to even
+    assert one(0x3F808001) == 0x3F81 and one(0x3F807FFF) == 0x3F80
+    assert one(0x7F7FFFFF) == 0x7F80 and one(0xFF7FFFFF) == 0xFF80       # largest finite -> inf
+    assert one(0x00008000) == 0x0000 and one(0x00018000) == 0x0002       # subnormal ties
+    # values that fit are unchanged, and the round trip through from_bf16_bits is the identity
+    k = rng.integers(0, 2 ** 16, size=5000, dtype=np.uint64).astype(np.uint16)
+    k = k[(k & 0x7FFF) <= 0x7F80]
+    assert np.array_equal(oracle.to_bf16_bits(oracle.from_bf16_bits(k)), k)
+    assert np.array_equal(oracle.from_bf16_bits(k).view(np.uint32), k.astype(np.uint32) << 16)
+    # error bound of round-to-nearest: half an ulp of the 8-bit significand, at most 2^-8 relative
+    y = (rng.standard_normal(20000) * 10.0 ** rng.uniform(-20, 20, 20000)).astype(np.float32)
+    err = np.abs(oracle.from_bf16_bits(oracle.to_bf16_bits(y)).astype(np.float64) - y)
+    assert np.all(err <= np.abs(y.astype(np.float64)) * 2.0 ** -8)
+    nan = oracle.to_bf16_bits(np.array([np.nan, -np.nan], dtype=np.float32))
+    assert np.all((nan & 0x7FFF) > 0x7F80)
+
+
+@pytest.mark.parametrize("direct", [False, True])
+def test_bf16_forward_slots_are_the_rounded_fp32_ones(oracle, direct):
+    """Only the forward slots change format: same tiles written, each value the fp32 one
+    rounded once; R, the owned chunk and the tracker are those of the fp32 path."""
+    M, N, K, P, r, tm, tn = 10, 24, 24, 3, 1, 4, 4
+    a, b, inc = wl.make_inputs(wl.make_shape("s", M, N, K, P, r, tm, tn), seed=77)
+    W = N // P
+    tpc = oracle.tiles_per_chunk(M, N, P, tm, tn)
+    for limit in (-1, tpc + 3):
+        f32 = oracle.fused_path(a, b, inc, P, r, tm, tn, fwd_direct=direct, tile_limit=limit,
+                                fwd_init=np.full((P - 1, M, W), -7.0, np.float32))
+        b16 = oracle.fused_path(a, b, inc, P, r, tm, tn, fwd_direct=direct, tile_limit=limit,
+                                fwd_init=np.full((P - 1, M, W), 0xABCD, np.uint16), fwd_bf16=True)
+        written = f32["fwd"] != -7.0
+        assert b16["fwd"].dtype == np.uint16
+        assert np.array_equal(b16["fwd"][written], oracle.to_bf16_bits(f32["fwd"][written]))
+        assert np.all(b16["fwd"][~written] == 0xABCD)
+        assert np.array_equal(b16["R"], f32["R"]) and np.array_equal(b16["owned"], f32["owned"])
+        for key in ("counter", "ready", "queue"):
+            assert np.array_equal(b16[key], f32[key])
+        # a forwarded value is within half a bf16 ulp of the exact sum it stands for
+        S = oracle.reduce_rows(oracle.gemm_rows(a, b), inc, P)
+        for s in range(P - 1):
+            c = int(f32["order"][s])
+            w_ = written[s]
+            exact = S[:, c * W:(c + 1) * W][w_].astype(np.float64)
+            assert np.all(np.abs(oracle.from_bf16_bits(b16["fwd"][s][w_]) - exact)
+                          <= np.abs(exact) * 2.0 ** -8 + 1e-30)
+    # the triggered transfers of two-writer mode round the same way
+    tw = oracle.fused_path(a, b, inc, P, r, tm, tn, two_writers=True)
+    rel = oracle.release_ready(tw["R"], np.zeros((P - 1, M, W), np.uint16), tw["ready"], P, r,
+                               fwd_bf16=True)
+    full = oracle.fused_path(a, b, inc, P, r, tm, tn, fwd_bf16=True)
+    assert np.array_equal(rel, full["fwd"])
