@@ -28,12 +28,16 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {("gpt3_outproj", "direct"): 631.4e6}
 
 
-def algorithmic_bytes(w, direct):
+def algorithmic_bytes(w, direct, fwd_bf16=False):
     """Bytes the method must move: A and B once, incoming once, result once; the default
-    release adds one read and one write of every forwarded chunk."""
+    release adds one read and one write of every forwarded chunk.  bfloat16 forward slots
+    halve the bytes written to them."""
+    fwd_part = w.M * w.N * (w.tp - 1) / w.tp          # elements that are forwarded
     base = 2.0 * w.M * w.K + 2.0 * w.K * w.N + 8.0 * w.M * w.N
     if not direct:
-        base += 8.0 * w.M * w.N * (w.tp - 1) / w.tp
+        base += 8.0 * fwd_part
+    if fwd_bf16:
+        base -= 2.0 * fwd_part
     return base
 
 
@@ -66,6 +70,8 @@ def main():
                     help="direct: forwarded sums go straight to the forward buffer "
                          "(T3_FLAG_FWD_DIRECT); copy: sums are added in place and release "
                          "workgroups copy each triggered chunk to its forward slot")
+    ap.add_argument("--fwd-bf16", action="store_true",
+                    help="forward slots in bfloat16 (T3_FLAG_FWD_BF16); the default run keeps fp32")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step as a captured HIP graph instead of launching its kernels "
@@ -96,7 +102,8 @@ def main():
     fwd = torch.zeros((w.tp - 1, w.M, w.W), dtype=torch.float32, device=dev)
     C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
     track = torch.zeros(t3.t3_track_words(w.tp), dtype=torch.int32, device=dev)
-    flags = t3.T3_FLAG_FWD_DIRECT if args.direct else 0
+    fmt = t3.T3_FLAG_FWD_BF16 if args.fwd_bf16 else 0
+    flags = (t3.T3_FLAG_FWD_DIRECT if args.direct else 0) | fmt
     p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n, flags=flags)
     tile = (w.tile_m, w.tile_n) if w.tile_m else t3.t3_default_tile(p)
 
@@ -188,7 +195,7 @@ def main():
     # The other release mode, fused and unfused, timed the same way (reported beside the main
     # figures: `copy` is the literal add-in-place-then-release path, `direct` writes forwarded
     # sums straight to their forward slots).
-    o_flags = 0 if args.direct else t3.T3_FLAG_FWD_DIRECT
+    o_flags = (0 if args.direct else t3.T3_FLAG_FWD_DIRECT) | fmt
     po = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n, flags=o_flags)
 
     def o_fused():
@@ -213,19 +220,19 @@ def main():
     assert tr["error"] == 0, "tracker error in the other release mode"
 
     tflops = w.flop / t_fused / 1e12
-    bytes_alg = algorithmic_bytes(w, args.direct)
+    bytes_alg = algorithmic_bytes(w, args.direct, args.fwd_bf16)
     t_mfma = w.flop / (PEAK_BF16_TFLOPS * 1e12)
     t_hbm = bytes_alg / (PEAK_HBM_GBS * 1e9)
     if t_mfma >= t_hbm:
         ach = w.flop / (k_avg * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.release))}
+                "traffic": None if args.fwd_bf16 else MEASURED_TRAFFIC_BYTES.get((w.name, args.release))}
     else:
         ach = bytes_alg / (k_avg * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.release))}
+                "traffic": None if args.fwd_bf16 else MEASURED_TRAFFIC_BYTES.get((w.name, args.release))}
     roof.update(kernel="gemm_tile_kernel<%d,%d,fused>" % tuple(tile),
                 kernel_ms_avg=k_avg, kernel_ms_min=k_ms[0], kernel_ms_median=k_ms[len(k_ms) // 2],
                 algorithmic_bytes=bytes_alg, flop=w.flop)
@@ -238,6 +245,7 @@ def main():
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "tp": w.tp, "rank": w.rank,
                    "tile": list(tile),
                    "release": "direct" if args.direct else "copy",
+                   "fwd": "bf16" if args.fwd_bf16 else "fp32",
                    "launch": "hip_graph" if args.graph else "eager"},
         "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "unfused_ms_per_step": t_unfused * 1e3,

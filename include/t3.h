@@ -68,6 +68,12 @@ typedef enum {
                                        T3_FLAG_STEP0_STORE_ONLY chunk order[0] has no upstream update.
                                        Not combinable with T3_FLAG_FWD_DIRECT.                        */
 
+#define T3_FLAG_FWD_BF16 8u         /* the forward slots hold bfloat16 instead of fp32: what is sent
+                                       on is the fp32 sum rounded to nearest even, the 16-bit format
+                                       activations travel in under mixed precision (Sec. 5.2).  With
+                                       any release mode; R and the owned chunk stay fp32.  N/tp must
+                                       be a multiple of 8 (T3_ERR_ALIGN)                             */
+
 typedef struct {
   int32_t M, N, K;        /* tokens, hidden size, slice width of this rank                           */
   int32_t tp, rank;       /* ring size and this rank's position                                      */
@@ -179,12 +185,14 @@ t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
  *                           from R by release workgroups of the same launch, which wait on
  *                           the chunk's ready flag) and left untouched otherwise.  T3_FLAG_FWD_DIRECT: executed tiles
  *                           are written as they finish.  May be NULL if tp == 1.
+ *                           With T3_FLAG_FWD_BF16 (here and in t3_rs_reduce / t3_release_chunks)
+ *                           the same array holds bfloat16: [tp-1][M][W] of 2 bytes.
  *   track                   tracker state (reset once; launches sharing it must be ordered
  *                           on one stream)
  * fp32 accumulation order is unspecified; integer outputs are exact.
  */
 t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, float *R,
-                           float *fwd, uint32_t *track, void *stream);
+                           void *fwd, uint32_t *track, void *stream);
 
 /* Unfused baseline, step 1: the plain sliced GEMM (Sec. 2.4).  C fp32 [M][ldc] out.
    tp/rank/tile_limit order the tiles exactly as in the fused call; flags are ignored. */
@@ -193,7 +201,7 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
 /* Unfused baseline, step 2: the reduce-scatter's reduction kernel (Sec. 2.3, the
    baseline of Sec. 4.3): reads C and R, writes what t3_gemm_rs_fused would have
    written to R / fwd, and drives the same tracker, tile by tile in the same order. */
-t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd,
+t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, void *fwd,
                        uint32_t *track, void *stream);
 
 /*
@@ -218,7 +226,7 @@ t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd
  */
 t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *R,
                              uint32_t *track, void *stream);
-t3_status t3_release_chunks(const t3_problem *p, const float *R, float *fwd,
+t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
                             const uint32_t *track, void *stream);
 
 const char *t3_status_string(t3_status s);

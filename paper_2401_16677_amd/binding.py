@@ -17,6 +17,7 @@ T3_B_NK, T3_B_KN = 0, 1
 T3_FLAG_STEP0_STORE_ONLY = 1
 T3_FLAG_FWD_DIRECT = 2
 T3_FLAG_TWO_WRITERS = 4
+T3_FLAG_FWD_BF16 = 8
 
 EXPORTS = ["t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
            "t3_track_words", "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",

@@ -79,7 +79,7 @@ enum Need { kNeedAB = 1, kNeedR = 2, kNeedC = 4, kNeedFwd = 8, kNeedTrack = 16,
 
 // Validates everything and fills the plan.  *empty is set when there is nothing to launch.
 t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B, const float *C,
-                    float *R, float *fwd, uint32_t *track, t3k::Plan *plan, int32_t *tm,
+                    float *R, void *fwd, uint32_t *track, t3k::Plan *plan, int32_t *tm,
                     int32_t *tn, bool *empty) {
   t3_status st = check_shape(p);
   if (st != T3_OK) return st;
@@ -94,7 +94,8 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   if ((need & kNeedTrack) && !track) return T3_ERR_NULL;
   if ((need & kNeedFwd) && p->tp > 1 && !fwd && !(two_writers && (need & kNeedAB)))
     return T3_ERR_NULL;                         // (the fused call releases nothing with two writers)
-  if (p->flags & ~(T3_FLAG_STEP0_STORE_ONLY | T3_FLAG_FWD_DIRECT | T3_FLAG_TWO_WRITERS))
+  if (p->flags & ~(T3_FLAG_STEP0_STORE_ONLY | T3_FLAG_FWD_DIRECT | T3_FLAG_TWO_WRITERS |
+                   T3_FLAG_FWD_BF16))
     return T3_ERR_UNSUPPORTED;
   if (two_writers && direct) return T3_ERR_UNSUPPORTED;   // both writers must target R
   if ((need & kNeedTwoWriters) && !two_writers) return T3_ERR_UNSUPPORTED;
@@ -135,6 +136,8 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
     if ((int64_t)p->M * p->ldc * 4 >= (1ll << 32)) return T3_ERR_UNSUPPORTED;
   }
   if ((need & kNeedFwd) && fwd && !aligned16(fwd)) return T3_ERR_ALIGN;
+  // bfloat16 forward slots move 8 elements per 16-byte access
+  if ((need & kNeedFwd) && fused_like && (p->flags & T3_FLAG_FWD_BF16) && W % 8) return T3_ERR_ALIGN;
 
   const int64_t Mt = ceil_div(p->M, *tm), Wt = ceil_div(W, *tn);
   const int64_t tpc = Mt * Wt, T = tpc * p->tp;
@@ -146,7 +149,7 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.B = static_cast<const uint16_t *>(B);
   q.C = C;
   q.R = R;
-  q.fwd = fwd;
+  q.fwd = static_cast<float *>(fwd);     // (bfloat16 under T3_FLAG_FWD_BF16)
   q.track = track;
   q.lda = p->lda;
   q.ldb = p->ldb;
@@ -358,7 +361,7 @@ t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream) {
 }
 
 t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, float *R,
-                           float *fwd, uint32_t *track, void *stream) {
+                           void *fwd, uint32_t *track, void *stream) {
   t3k::Plan q;
   int32_t tm, tn;
   bool empty = false;
@@ -384,7 +387,7 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
   return launched();
 }
 
-t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, float *fwd,
+t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, void *fwd,
                        uint32_t *track, void *stream) {
   t3k::Plan q;
   int32_t tm, tn;
@@ -432,7 +435,7 @@ t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *
   return launched();
 }
 
-t3_status t3_release_chunks(const t3_problem *p, const float *R, float *fwd,
+t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
                             const uint32_t *track, void *stream) {
   t3k::Plan q;
   int32_t tm, tn;

@@ -39,6 +39,7 @@ constexpr int kSpinLimit = 1 << 22;   // polls of a release workgroup before it 
 constexpr uint32_t kFlagStep0StoreOnly = 1u;
 constexpr uint32_t kFlagFwdDirect = 2u;
 constexpr uint32_t kFlagTwoWriters = 4u;
+constexpr uint32_t kFlagFwdBf16 = 8u;
 
 enum Mode { kModeGemm = 0, kModeFused = 1 };
 enum Role { kRoleNone = 0, kRoleTile = 1, kRoleRelease = 2 };
@@ -210,6 +211,60 @@ __device__ inline f32x4 load_stream(__amdgpu_buffer_rsrc_t r, uint32_t lane_off,
   return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)blk_off, kAuxNt));
 }
 
+// fp32 -> bfloat16, round to nearest even (v_cvt_pk_bf16_f32): the 16-bit format a forward slot
+// may hold (activations under mixed precision, Sec. 5.2).
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+__device__ inline u32x2 pack_bf16(f32x4 v) {
+  return __builtin_bit_cast(u32x2, __builtin_convertvector(v, bf16x4));
+}
+__device__ inline u32x4 pack_bf16(f32x4 lo, f32x4 hi) {
+  const u32x2 a = pack_bf16(lo), b = pack_bf16(hi);
+  return u32x4{a[0], a[1], b[0], b[1]};
+}
+
+// Rows r0, r0 + step, ... < r_end of chunk c of R into forward slot `slot`, one wavefront per
+// row, 16 bytes per lane: the copy a trigger starts (Sec. 4.2.2).  The slot holds fp32, or
+// bfloat16 under kFlagFwdBf16.
+__device__ inline void copy_chunk_rows(const Plan &p, int slot, int c, int r0, int r_end, int step) {
+  const int lane = threadIdx.x & 63;
+  if (p.flags & kFlagFwdBf16) {
+    const int W8 = p.W >> 3;
+    for (int r = r0; r < r_end; r += step) {
+      const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
+      u32x4 *dst = (u32x4 *)((uint16_t *)p.fwd + ((int64_t)slot * p.M + r) * p.W);
+      for (int c0 = lane; c0 < W8; c0 += 2 * 64) {
+        f32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          if (c0 + u * 64 < W8) {
+            v[2 * u] = __builtin_nontemporal_load(src + 2 * (c0 + u * 64));
+            v[2 * u + 1] = __builtin_nontemporal_load(src + 2 * (c0 + u * 64) + 1);
+          }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          if (c0 + u * 64 < W8)
+            __builtin_nontemporal_store(pack_bf16(v[2 * u], v[2 * u + 1]), dst + c0 + u * 64);
+      }
+    }
+    return;
+  }
+  const int W4 = p.W >> 2;
+  for (int r = r0; r < r_end; r += step) {
+    const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
+    f32x4 *dst = (f32x4 *)(p.fwd + ((int64_t)slot * p.M + r) * p.W);
+    for (int c0 = lane; c0 < W4; c0 += 4 * 64) {
+      f32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * 64 < W4) v[u] = __builtin_nontemporal_load(src + c0 + u * 64);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * 64 < W4) __builtin_nontemporal_store(v[u], dst + c0 + u * 64);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Track & trigger (Sec. 4.2).  Called by all threads of a workgroup after the tile's stores
 // have been issued.  Tile results are written with agent-scope stores; once they have been
@@ -270,22 +325,8 @@ __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of R
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int W4 = p.W >> 2;
-  const int r_end = min(p.M, (agent + 1) * p.rows_per_agent);
-  for (int r = agent * p.rows_per_agent + wave; r < r_end; r += (int)(blockDim.x >> 6)) {
-    const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
-    f32x4 *dst = (f32x4 *)(p.fwd + ((int64_t)slot * p.M + r) * p.W);
-    for (int c0 = lane; c0 < W4; c0 += 4 * 64) {
-      f32x4 v[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (c0 + u * 64 < W4) v[u] = __builtin_nontemporal_load(src + c0 + u * 64);
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (c0 + u * 64 < W4) __builtin_nontemporal_store(v[u], dst + c0 + u * 64);
-    }
-  }
+  copy_chunk_rows(p, slot, c, agent * p.rows_per_agent + (int)(threadIdx.x >> 6),
+                  min(p.M, (agent + 1) * p.rows_per_agent), (int)(blockDim.x >> 6));
   __builtin_amdgcn_s_waitcnt(kWaitAll);
   __syncthreads();
   if (threadIdx.x == 0) trk_workgroup_done(p, t);
@@ -703,6 +744,47 @@ void gemm_tile_kernel(const Plan p) {
     out_base = p.R;
     col_org = 0;
   }
+  if (to_fwd && (p.flags & kFlagFwdBf16)) {
+    // Forward slot in bfloat16: a row of the wavefront tile (64 columns) is one 128-byte line.
+    // Row of blocks by row of blocks through LDS: the lane's four rounded sums of each block
+    // (8 bytes) go to row (lane & 15), columns 16 j + 4 (lane >> 4) of a 16-row x 128-byte
+    // image, 16-byte chunk k of row r kept at position k ^ ((r >> 1) & 7) (both sides free of
+    // bank conflicts); read back linearly, each store instruction covers 8 rows x 128 bytes.
+    static_assert(FN == 4, "a wavefront tile is 64 columns wide");
+    __syncthreads();
+    char *scr = lds + wave * (kRingSlots * 1024);
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int arow = lane_e & 15, aq = lane_e >> 4;
+    int w_off[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+      w_off[j] = arow * 128 + (((2 * j + (aq >> 1)) ^ ((arow >> 1) & 7)) << 4) + ((aq & 1) << 3);
+    const __amdgpu_buffer_rsrc_t o16 =
+        make_rsrc((const uint16_t *)p.fwd + (int64_t)tl.s * p.M * p.W, (uint32_t)p.M * p.W * 2u);
+    int l_row[2], l_col[2];
+    uint32_t l_off[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      l_row[h] = 8 * h + (lane_e >> 3);
+      l_col[h] = 8 * ((lane_e & 7) ^ ((l_row[h] >> 1) & 7));
+      l_off[h] = ((uint32_t)(rw0 + l_row[h]) * (uint32_t)p.W + (uint32_t)(cw0 - col_lo + l_col[h])) * 2u;
+    }
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      char *img = scr + (i & 1) * 2048;
+#pragma unroll
+      for (int j = 0; j < FN; ++j) *(u32x2 *)(img + w_off[j]) = pack_bf16(acc[i][j]);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const u32x4 v = *(const u32x4 *)(img + h * 1024 + lane_e * 16);
+        if (full || (rw0 + 16 * i + l_row[h] < p.M && cw0 + l_col[h] < col_hi))
+          __builtin_amdgcn_raw_buffer_store_b128(v, o16, (int)l_off[h],
+                                                 (int)((uint32_t)(16 * i) * (uint32_t)p.W * 2u), kAuxSc1);
+      }
+      if (i % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
   const __amdgpu_buffer_rsrc_t out_rsrc = make_rsrc(out_base, (uint32_t)p.M * ld_out * 4u);
   // Pair by pair through LDS (the stages are free now; each wavefront uses 4 KiB of its own):
   // written in the accumulator layout, read back linearly, stored as 8 rows x 128 bytes.
@@ -752,6 +834,7 @@ void gemm_tile_kernel(const Plan p) {
     if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
   }
   }
+  }
 
   if (MODE == kModeFused) {
     if (nkf == 0) flush_pending();               // (no main loop ran: nothing was counted on the way)
@@ -786,6 +869,27 @@ __global__ __launch_bounds__(kThreads) void reduce_tile_kernel(const Plan p) {
   const bool to_fwd = (p.flags & kFlagFwdDirect) && tl.c != p.own;
   float *out_base = to_fwd ? p.fwd + (int64_t)tl.s * p.M * p.W + (n0 - col_lo) : p.R + n0;
   const int64_t ld_out = to_fwd ? p.W : p.ldr;
+  if (to_fwd && (p.flags & kFlagFwdBf16)) {
+    // bfloat16 forward slot: eight sums = 16 bytes per lane
+    const int cols8 = cols4 >> 1;
+    uint16_t *out16 = (uint16_t *)p.fwd + (int64_t)tl.s * p.M * p.W + (n0 - col_lo);
+    for (int e = tid; e < rows * cols8; e += kThreads) {
+      const int rr = e / cols8, cc = e - rr * cols8;
+      const int64_t row = m0 + rr;
+      const f32x4 *c = (const f32x4 *)(p.C + row * p.ldc + n0) + 2 * cc;
+      const f32x4 *r = (const f32x4 *)(p.R + row * p.ldr + n0) + 2 * cc;
+      f32x4 lo = __builtin_nontemporal_load(c), hi = __builtin_nontemporal_load(c + 1);
+      if (!store_only) {
+        lo += __builtin_nontemporal_load(r);
+        hi += __builtin_nontemporal_load(r + 1);
+      }
+      const u32x4 v = pack_bf16(lo, hi);
+      asm volatile("global_store_dwordx4 %0, %1, off sc1"
+                   : : "v"((u32x4 *)(out16 + row * p.W) + cc), "v"(v) : "memory");
+    }
+    track_tile(p, trk, tl.c);
+    return;
+  }
   const int total = rows * cols4;
   for (int e = tid; e < total; e += kThreads) {
     const int rr = e / cols4, cc = e - rr * cols4;
@@ -854,14 +958,8 @@ __global__ __launch_bounds__(kThreads) void release_ready_kernel(const Plan p) {
   int c = p.rank + slot;
   if (c >= p.P) c -= p.P;
   if (__hip_atomic_load(bank + p.P + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int W4 = p.W >> 2;
-  const int r_end = min(p.M, (agent + 1) * p.rows_per_agent);
-  for (int r = agent * p.rows_per_agent + wave; r < r_end; r += kThreads / 64) {
-    const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
-    f32x4 *dst = (f32x4 *)(p.fwd + ((int64_t)slot * p.M + r) * p.W);
-    for (int c0 = lane; c0 < W4; c0 += 64) dst[c0] = __builtin_nontemporal_load(src + c0);
-  }
+  copy_chunk_rows(p, slot, c, agent * p.rows_per_agent + (int)(threadIdx.x >> 6),
+                  min(p.M, (agent + 1) * p.rows_per_agent), kThreads / 64);
 }
 
 // Clears tracker state: both banks (queue entries to empty, the rest to 0), gen and error to 0.

@@ -6,6 +6,7 @@ import torch
 from paper_2401_16677_amd import binding as t3
 
 SENTINEL = -7.0
+SENTINEL_BF16 = 0xABCD          # bit pattern a bfloat16 forward slot is filled with beforehand
 
 
 def to_dev_bits(bits):
@@ -15,7 +16,8 @@ def to_dev_bits(bits):
 def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfused=False,
             ldr_pad=0, lda_pad=0, tile_begin=0, b_kn=False):
     """One call of the fused path (or the unfused GEMM-then-reduce pair).  Returns a dict
-    with R, fwd, counter, ready, queue, queue_len (numpy) and, for unfused, C."""
+    with R, fwd (uint16 bit patterns under T3_FLAG_FWD_BF16), counter, ready, queue, queue_len
+    (numpy) and, for unfused, C."""
     M, K = a_bits.shape
     N = b_bits.shape[0]
     W = N // tp
@@ -37,8 +39,13 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
     R = torch.full((max(M, 1), ldr), 123.0, dtype=torch.float32, device=dev)
     if M:
         R[:M, :N] = torch.from_numpy(inc).to(dev)
-    fwd = torch.full((max(tp - 1, 1), max(M, 1), max(W, 1)), SENTINEL, dtype=torch.float32,
-                     device=dev)
+    bf16 = bool(flags & t3.T3_FLAG_FWD_BF16)
+    if bf16:      # int16 holding the sentinel's bit pattern
+        fwd = torch.full((max(tp - 1, 1), max(M, 1), max(W, 1)), SENTINEL_BF16 - 65536,
+                         dtype=torch.int16, device=dev)
+    else:
+        fwd = torch.full((max(tp - 1, 1), max(M, 1), max(W, 1)), SENTINEL, dtype=torch.float32,
+                         device=dev)
     track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
     p = t3.problem(M, N, K, tp, rank, tile[0], tile[1], lda=K + lda_pad, ldb=ldb,
                    b_layout=t3.T3_B_KN if b_kn else t3.T3_B_NK,
@@ -58,6 +65,8 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
     out["R"] = Rh[:M, :N]
     out["R_pad"] = Rh[:M, N:]
     out["fwd"] = fwd.cpu().numpy()[:max(tp - 1, 0), :M, :W]
+    if bf16:
+        out["fwd"] = out["fwd"].view(np.uint16)
     tr = t3.read_track(track, tp)
     out.update(counter=tr["counter"], ready=tr["ready"], queue=tr["queue"],
                queue_len=tr["queue_len"], error=tr["error"], gen=tr["gen"])

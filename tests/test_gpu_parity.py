@@ -367,6 +367,93 @@ def test_float_multi_tile_ragged(gpu, oracle, tile):
     _check_ints(got, want, tp, want["own"])
 
 
+# ---------------------------------------------------------------- bfloat16 forward slots
+
+@pytest.mark.parametrize("mode", ["fused_direct", "fused_copy", "unfused_direct", "unfused_copy"])
+@pytest.mark.parametrize("step0", [False, True])
+@pytest.mark.parametrize("case", EXACT_CASES)
+def test_bf16_forward_slots_bit_exact(gpu, oracle, case, step0, mode):
+    """T3_FLAG_FWD_BF16: what is forwarded is the fp32 sum rounded to nearest even (Sec. 5.2's
+    16-bit activations); with integer inputs the fp32 sums are exact, so every bit is fixed."""
+    M, N, K, tp, rank, tile = case
+    assert (N // tp) % 8 == 0
+    direct, unfused = mode.endswith("direct"), mode.startswith("unfused")
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=900 + M)
+    inc = inc * np.float32(257.0)      # sums well past 256: most need rounding to 8 bits
+    print(f"case={case} step0={step0} mode={mode}", flush=True)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, step0_store_only=step0, fwd_direct=direct,
+                             fwd_bf16=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL_BF16, np.uint16))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, unfused=unfused, ldr_pad=4, lda_pad=8,
+                      flags=_flags(step0, direct) | t3.T3_FLAG_FWD_BF16)
+    assert got["fwd"].dtype == np.uint16 and np.array_equal(got["fwd"], want["fwd"])
+    assert np.array_equal(got["R"], want["R"]) and np.all(got["R_pad"] == 123.0)
+    _check_ints(got, want, tp, want["own"])
+    if tp > 1 and not step0:      # the case does exercise rounding (a stored-only first chunk
+        # holds the small integers of C alone)
+        exact = oracle.fused_path(a, b, inc, tp, rank, *tile, step0_store_only=step0,
+                                  fwd_direct=direct)["fwd"]
+        assert np.any(oracle.from_bf16_bits(want["fwd"]) != exact)
+
+
+@pytest.mark.parametrize("direct", [False, True])
+def test_bf16_forward_slots_partial_range_and_float(gpu, oracle, direct):
+    """A tile range leaves the other elements of the bfloat16 slots untouched; float inputs agree
+    to the fp32 path's tolerance plus one rounding to 8 bits."""
+    M, N, K, tp, rank, tile = 700, 2080, 328, 4, 3, (256, 128)
+    w = wl.make_shape("ragged", M, N, K, tp, rank, *tile)
+    a, b, inc = wl.make_inputs(w, seed=78)
+    W = N // tp
+    tpc = oracle.tiles_per_chunk(M, N, tp, *tile)
+    sent = np.full((tp - 1, M, W), gpu.SENTINEL_BF16, np.uint16)
+    for begin, limit in ((0, -1), (0, tpc + 5), (2, tpc + 5)):
+        want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=direct, fwd_bf16=True,
+                                 tile_begin=begin, tile_limit=limit, fwd_init=sent)
+        got = gpu.run_gpu(a, b, inc, tp, rank, tile, tile_begin=begin, tile_limit=limit,
+                          flags=_flags(False, direct) | t3.T3_FLAG_FWD_BF16)
+        written = want["fwd"] != gpu.SENTINEL_BF16
+        assert np.array_equal(got["fwd"] != gpu.SENTINEL_BF16, written)
+        assert gpu.rel_err(got["R"], want["R"]) <= EXPECT
+        _check_ints(got, want, tp, want["own"])
+        if not written.any():      # (a range that completes no chunk releases nothing by copy)
+            assert not direct and begin > 0
+            continue
+        g, x = oracle.from_bf16_bits(got["fwd"][written]), oracle.from_bf16_bits(want["fwd"][written])
+        # fp32 sums that differ in their last places (by up to 1e-4 of the largest sum where
+        # terms cancel) may round to neighbouring bfloat16 values
+        assert np.all(np.abs(g.astype(np.float64) - x)
+                      <= np.abs(x) * 2.0 ** -7 + 1e-4 * np.abs(x).max())
+        assert np.mean(got["fwd"][written] == want["fwd"][written]) > 0.99
+        assert gpu.rel_err(g, x) <= EXPECT + 2.0 ** -9
+
+
+def test_bf16_forward_slots_two_writer_release(gpu, oracle):
+    """The triggered transfers of two-writer mode (t3_release_chunks) round the same way."""
+    import torch
+    M, N, K, tp, rank, tile = 300, 800, 200, 4, 2, (128, 128)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=950)
+    inc = inc * np.float32(257.0)
+    W = N // tp
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    INC = torch.from_numpy(inc).to(dev)
+    R = torch.zeros((M, N), dtype=torch.float32, device=dev)
+    fwd = torch.full((tp - 1, M, W), gpu.SENTINEL_BF16 - 65536, dtype=torch.int16, device=dev)
+    track = torch.zeros(t3.t3_track_words(tp), dtype=torch.int32, device=dev)
+    p = t3.problem(M, N, K, tp, rank, *tile, ldc=N,
+                   flags=t3.T3_FLAG_TWO_WRITERS | t3.T3_FLAG_FWD_BF16)
+    t3.t3_track_reset(tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, None, track)
+    t3.t3_upstream_update(p, INC, R, track)
+    t3.t3_release_chunks(p, R, fwd, track)
+    torch.cuda.synchronize()
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, two_writers=True)
+    rel = oracle.release_ready(want["R"], np.full((tp - 1, M, W), gpu.SENTINEL_BF16, np.uint16),
+                               want["ready"], tp, rank, fwd_bf16=True)
+    assert np.array_equal(R.cpu().numpy(), want["R"])
+    assert np.array_equal(fwd.cpu().numpy().view(np.uint16), rel)
+
+
 def test_default_tile_and_k_zero_and_empty(gpu, oracle):
     # K = 0: C is zero, the path degenerates to the partition of the incoming data
     M, N, tp, rank = 128, 512, 4, 1

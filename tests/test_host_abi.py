@@ -98,7 +98,6 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert _fused_status(t3.problem(**{**ok, "K": 200}, b_layout=t3.T3_B_KN)) == t3.T3_ERR_UNSUPPORTED
     assert _fused_status(t3.problem(**{**ok, "N": 1008}, b_layout=t3.T3_B_KN)) == t3.T3_ERR_ALIGN  # W = 252
     assert _fused_status(t3.problem(**ok, b_layout=t3.T3_B_KN, ldb=512)) == t3.T3_ERR_BAD_SHAPE
-    assert _fused_status(t3.problem(**ok, flags=8)) == t3.T3_ERR_UNSUPPORTED
     assert _fused_status(t3.problem(**ok, b_layout=7)) == t3.T3_ERR_BAD_SHAPE
     # R of 4 GiB or more (32-bit byte offsets in the kernels): refused, nothing launched
     big = dict(M=65536, N=16384, K=64, tp=4, rank=0, tile_m=256, tile_n=256)
@@ -121,6 +120,10 @@ def test_bad_arguments_are_refused_before_any_launch():
     pw = t3.problem(**ok, flags=t3.T3_FLAG_TWO_WRITERS)
     assert L.t3_rs_reduce(ctypes.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), vp(0)) == \
         t3.T3_ERR_UNSUPPORTED
+    # bfloat16 forward slots: chunks of a multiple of 8 columns; unknown flag bits are refused
+    assert _fused_status(t3.problem(**{**ok, "N": ok["tp"] * 12}, flags=t3.T3_FLAG_FWD_BF16)) == \
+        t3.T3_ERR_ALIGN
+    assert _fused_status(t3.problem(**ok, flags=16)) == t3.T3_ERR_UNSUPPORTED
     # split-K needs the atomic updates of two-writer mode and a full K-slab per part
     assert _fused_status(t3.problem(**ok, split_k=2)) == t3.T3_ERR_UNSUPPORTED
     assert _fused_status(t3.problem(**ok, split_k=8, flags=t3.T3_FLAG_TWO_WRITERS)) == \
