@@ -72,6 +72,13 @@ t3_status resolve_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
   return T3_OK;
 }
 
+// the kernels test the same flag bits under their own names
+static_assert(T3_FLAG_STEP0_STORE_ONLY == t3k::kFlagStep0StoreOnly &&
+                  T3_FLAG_FWD_DIRECT == t3k::kFlagFwdDirect &&
+                  T3_FLAG_TWO_WRITERS == t3k::kFlagTwoWriters && T3_FLAG_FWD_BF16 == t3k::kFlagFwdBf16,
+              "flag bits of the header and of the kernels");
+static_assert(sizeof(t3_problem) == 96, "layout documented in the header");
+
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 enum Need { kNeedAB = 1, kNeedR = 2, kNeedC = 4, kNeedFwd = 8, kNeedTrack = 16,

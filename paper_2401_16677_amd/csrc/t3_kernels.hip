@@ -731,7 +731,7 @@ void gemm_tile_kernel(const Plan p) {
     }
   }
 
-  // ---- epilogue: one 16-byte agent-scope store per block
+  // ---- epilogue: the tile leaves in whole 128-byte lines, agent-scope (write-through) stores
   const float *out_base;  // uniform: R, C, or the chunk's forward slot
   uint32_t ld_out;
   int col_org;            // column the base's rows start at
