@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by the same counters' reading of a plain copy (profiles/*_hbm_traffic.txt says how).
 # Keyed by (workload, release); None = not measured since the kernel last changed.
-MEASURED_TRAFFIC_BYTES = {("gpt3_outproj", "direct"): 630.4e6}
+MEASURED_TRAFFIC_BYTES = {("gpt3_outproj", "direct"): 630.7e6}
 
 
 def algorithmic_bytes(w, direct, fwd_bf16=False):
@@ -81,8 +81,9 @@ def main():
                          "one by one (a step here is one or two kernels: back-to-back launches keep "
                          "the queue full, a graph launch per step leaves a gap between steps)")
     ap.add_argument("--traffic-probe", action="store_true",
-                    help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs: launch 5 x [a "
-                         "plain device copy of the M x N fp32 buffer, the fused kernel] and exit")
+                    help="for `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE, MFMA counters): launch "
+                         "5 x [a plain device copy of the M x N fp32 buffer, the fused kernel, the "
+                         "unfused GEMM and reduction] and exit")
     args = ap.parse_args()
     args.direct = args.release == "direct"
     if args.gpus != 1:
@@ -124,6 +125,7 @@ def main():
         for _ in range(5):
             C.copy_(R)
             fused_step()
+            unfused_step()
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": w.name, "copy_bytes_each_way": 4 * w.M * w.N,
                           "launches": 5}))
