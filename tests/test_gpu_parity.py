@@ -454,6 +454,44 @@ def test_bf16_forward_slots_two_writer_release(gpu, oracle):
     assert np.array_equal(fwd.cpu().numpy().view(np.uint16), rel)
 
 
+def _random_case(rng):
+    tp = int(rng.integers(1, 7))
+    tile = [(128, 128), (256, 128), (128, 256), (256, 256)][int(rng.integers(0, 4))]
+    bf16 = bool(rng.integers(0, 2))
+    kn = bool(rng.integers(0, 2))
+    w_unit = 8 if (bf16 or kn) else 4
+    W = w_unit * int(rng.integers(1, 1 + 600 // w_unit))
+    M = int(rng.integers(1, 700))
+    K = 64 * int(rng.integers(1, 8)) if kn else 8 * int(rng.integers(1, 60))
+    return dict(M=M, N=W * tp, K=K, tp=tp, rank=int(rng.integers(0, tp)), tile=tile, bf16=bf16, kn=kn,
+                direct=bool(rng.integers(0, 2)), step0=bool(rng.integers(0, 2)),
+                unfused=bool(rng.integers(0, 4) == 0), ldr_pad=4 * int(rng.integers(0, 3)),
+                lda_pad=8 * int(rng.integers(0, 3)))
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_shapes_and_modes_bit_exact(gpu, oracle, seed):
+    """Seeded random shapes (ragged everywhere), tile shapes, layouts, release modes and forward
+    formats, within the documented limits; integer inputs, so everything is fixed to the bit."""
+    c = _random_case(np.random.default_rng(4000 + seed))
+    print(f"seed={seed} case={c}", flush=True)
+    M, N, K, tp, rank, tile = c["M"], c["N"], c["K"], c["tp"], c["rank"], c["tile"]
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=5000 + seed)
+    inc = inc * np.float32(33.0)
+    sent = (np.full((tp - 1, M, N // tp), gpu.SENTINEL_BF16, np.uint16) if c["bf16"]
+            else np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    want = oracle.fused_path(a, np.ascontiguousarray(b.T) if c["kn"] else b, inc, tp, rank, *tile,
+                             b_layout=oracle.B_KN if c["kn"] else oracle.B_NK,
+                             step0_store_only=c["step0"], fwd_direct=c["direct"],
+                             fwd_bf16=c["bf16"], fwd_init=sent)
+    flags = _flags(c["step0"], c["direct"]) | (t3.T3_FLAG_FWD_BF16 if c["bf16"] else 0)
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=flags, unfused=c["unfused"],
+                      ldr_pad=c["ldr_pad"], lda_pad=c["lda_pad"], b_kn=c["kn"])
+    assert np.array_equal(got["R"], want["R"]) and np.all(got["R_pad"] == 123.0)
+    assert np.array_equal(got["fwd"], want["fwd"])
+    _check_ints(got, want, tp, want["own"])
+
+
 def test_default_tile_and_k_zero_and_empty(gpu, oracle):
     # K = 0: C is zero, the path degenerates to the partition of the incoming data
     M, N, tp, rank = 128, 512, 4, 1
