@@ -663,6 +663,52 @@ def test_full_size_b_stored_k_by_n(gpu, oracle):
     assert max(errs) <= EXPECT
 
 
+@pytest.mark.parametrize("direct", [True, False])
+def test_full_size_bf16_forward_slots(gpu, oracle, direct):
+    """gpt3_outproj at full size with bfloat16 forward slots: sampled rows.  The slots hold the
+    rounding of what the fp32 path would have forwarded: within one bfloat16 step of the oracle's
+    rounding of its own sum, equal on nearly every element; the owned chunk stays fp32."""
+    import torch
+    w = wl.WORKLOADS["gpt3_outproj"]
+    a, b, inc = wl.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 2)
+    rows = np.array(sorted({0, w.M - 1} | set(rng.integers(0, w.M, 16).tolist())), dtype=np.int32)
+    S = oracle.reduce_rows(oracle.gemm_rows(a, b, rows=rows), inc, w.tp, rows=rows)
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    R = torch.from_numpy(inc).to(dev)
+    fwd = torch.full((w.tp - 1, w.M, w.W), gpu.SENTINEL_BF16 - 65536, dtype=torch.int16, device=dev)
+    track = torch.zeros(t3.t3_track_words(w.tp), dtype=torch.int32, device=dev)
+    p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n,
+                   flags=t3.T3_FLAG_FWD_BF16 | (t3.T3_FLAG_FWD_DIRECT if direct else 0))
+    t3.t3_track_reset(w.tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+    order, own = oracle.chunk_order(w.tp, w.rank)
+    tr = t3.read_track(track, w.tp)
+    assert np.all(tr["ready"] == 1) and tr["queue_len"] == w.tp - 1 and tr["error"] == 0
+    idx = torch.from_numpy(rows.astype(np.int64)).to(dev)
+    Rg = R.index_select(0, idx).cpu().numpy()
+    fg = fwd.index_select(1, idx).cpu().numpy().view(np.uint16)
+    W = w.W
+    same = []
+    for s, c in enumerate(int(x) for x in order):
+        want = S[:, c * W:(c + 1) * W]
+        if c == own:
+            assert gpu.rel_err(Rg[:, c * W:(c + 1) * W], want) <= EXPECT
+            continue
+        bits = oracle.to_bf16_bits(want)
+        got = fg[s]
+        same.append(np.mean(got == bits))
+        x = oracle.from_bf16_bits(bits).astype(np.float64)
+        assert np.all(np.abs(oracle.from_bf16_bits(got) - x) <= np.abs(x) * 2.0 ** -7 + 1e-4 * np.abs(x).max())
+        assert gpu.rel_err(oracle.from_bf16_bits(got), want) <= EXPECT + 2.0 ** -9
+    print(f"direct={direct}: fraction of identical bfloat16 values per slot {min(same):.5f}..{max(same):.5f}",
+          flush=True)
+    assert min(same) > 0.99
+    assert not bool((fwd == gpu.SENTINEL_BF16 - 65536).all(dim=2).any())
+
+
 def test_graph_replays_match_eager(gpu, oracle):
     """The step bench.py times (tracker reset + fused call) captured in a HIP graph: every
     replay, with eager work and synchronisation in between, must reproduce the eager result."""
