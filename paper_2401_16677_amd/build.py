@@ -35,5 +35,26 @@ def build(force=True, extra_flags=()):
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(ROOT, "tests", "c_abi_client.c")
+C_CLIENT = os.path.join(ROOT, "tests", "c_abi_client")
+
+
+def build_c_client(force=True):
+    """Compile tests/c_abi_client.c, a plain C11 user of include/t3.h, with gcc against the
+    built library and the HIP runtime (it is run by the GPU tests)."""
+    if not force and os.path.exists(C_CLIENT) and \
+            os.path.getmtime(C_CLIENT) >= max(os.path.getmtime(C_CLIENT_SRC), os.path.getmtime(LIB)):
+        return C_CLIENT
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"),
+           C_CLIENT_SRC, "-o", C_CLIENT, "-L", HERE, "-l:libt3.so",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_2401_16677_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    subprocess.run(cmd, check=True)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build())
+    print(build_c_client())

@@ -709,6 +709,18 @@ def test_full_size_bf16_forward_slots(gpu, oracle, direct):
     assert not bool((fwd == gpu.SENTINEL_BF16 - 65536).all(dim=2).any())
 
 
+@pytest.mark.parametrize("flags", [0, 2, 3])
+def test_plain_c_client_of_the_abi(gpu, flags):
+    """tests/c_abi_client.c: a C11 program that includes include/t3.h, links the library and the
+    HIP runtime, and checks every output word itself.  Run as a child process."""
+    import subprocess
+    from paper_2401_16677_amd import build as hip_build
+    exe = hip_build.build_c_client(force=False)
+    r = subprocess.run([exe, str(flags)], capture_output=True, text=True, timeout=100)
+    print(r.stdout, r.stderr, flush=True)
+    assert r.returncode == 0 and " 0 mismatches" in r.stdout
+
+
 def test_graph_replays_match_eager(gpu, oracle):
     """The step bench.py times (tracker reset + fused call) captured in a HIP graph: every
     replay, with eager work and synchronisation in between, must reproduce the eager result."""

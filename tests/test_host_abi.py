@@ -142,3 +142,12 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert t3.status_string(t3.T3_ERR_BAD_TILE) == "unsupported tile shape"
     with pytest.raises(t3.T3Error):
         t3.t3_chunk_order(4, 5)
+
+
+def test_header_compiles_as_c11_and_a_c_client_links():
+    """include/t3.h is a C header: tests/c_abi_client.c is compiled with gcc -std=c11 -Wall
+    -Werror against it and linked with the built library (running it needs a GPU)."""
+    import os
+    from paper_2401_16677_amd import build as hip_build
+    exe = hip_build.build_c_client(force=True)
+    assert os.path.exists(exe) and os.access(exe, os.X_OK)
