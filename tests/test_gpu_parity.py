@@ -454,6 +454,34 @@ def test_bf16_forward_slots_two_writer_release(gpu, oracle):
     assert np.array_equal(fwd.cpu().numpy().view(np.uint16), rel)
 
 
+EXTREME_CASES = [
+    # M, N,   K,  tp, rank, tile          what is extreme
+    (1, 256, 8, 64, 63, (128, 128)),      # one row, 64 chunks of 4 columns, K = one 16-byte piece
+    (1, 8, 64, 1, 0, (256, 256)),         # a single ragged tile, no ring
+    (257, 1032, 64, 3, 2, (256, 256)),    # one full tile row + one row; W = 344 = 256 + 88
+    (129, 520, 72, 1, 0, (128, 256)),     # K = one slab + 8
+    (640, 4096, 8, 32, 17, (256, 128)),   # 32 chunks, K below a slab: register path only
+    (2049, 768, 128, 2, 1, (256, 256)),   # 9 tile rows, last one a single row
+    (512, 12288, 64, 48, 47, (128, 128)), # 48 chunks, last rank
+]
+
+
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("case", EXTREME_CASES)
+def test_extreme_shapes_bit_exact(gpu, oracle, case, direct):
+    M, N, K, tp, rank, tile = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1300 + M + tp)
+    print(f"case={case} direct={direct}", flush=True)
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    for unfused in (False, True):
+        want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=direct, fwd_init=sent)
+        got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=_flags(False, direct), unfused=unfused,
+                          ldr_pad=8)
+        assert np.array_equal(got["R"], want["R"]) and np.all(got["R_pad"] == 123.0)
+        assert np.array_equal(got["fwd"], want["fwd"])
+        _check_ints(got, want, tp, want["own"])
+
+
 def _random_case(rng):
     tp = int(rng.integers(1, 7))
     tile = [(128, 128), (256, 128), (128, 256), (256, 256)][int(rng.integers(0, 4))]
