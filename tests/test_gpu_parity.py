@@ -749,6 +749,66 @@ def test_plain_c_client_of_the_abi(gpu, flags):
     assert r.returncode == 0 and " 0 mismatches" in r.stdout
 
 
+def test_largest_supported_buffers(gpu, oracle):
+    """R, C and the forward slot just below the documented 4 GiB limit (the kernels address them
+    with 32-bit byte offsets): M = 32768, N = 32760, so the last element sits at byte offset
+    4,293,918,716.  Integer inputs given by a formula; rows sampled from both ends and the
+    middle are compared bit for bit, fused and unfused, and the size one step further is refused."""
+    import torch
+    M, N, K, tp, rank, tile = 32768, 32760, 64, 2, 1, (256, 256)
+    assert M * N * 4 < 2 ** 32 < (M + 16) * N * 4
+    W = N // tp
+    a = wl.make_integer_inputs(M, 8, K, seed=1700)[0]          # (the generator's own incoming
+    b = wl.make_integer_inputs(8, N, K, seed=1701)[1]          # array would be 4 GiB: not drawn)
+    rows = np.array([0, 1, 255, 256, 16383, 16384, 21000, 32511, 32512, 32766, 32767], dtype=np.int64)
+    cols = np.arange(N, dtype=np.int64)
+    inc_rows = ((rows[:, None] * 131 + cols[None, :] * 7) % 2001 - 1000).astype(np.float32)
+    S = oracle.reduce_rows(oracle.gemm_rows(a, b, rows=rows.astype(np.int32)), inc_rows, tp)
+    dev = torch.device("cuda:0")
+
+    def fresh_R():
+        r = torch.arange(M, dtype=torch.int32, device=dev)[:, None] * 131
+        r = r + torch.arange(N, dtype=torch.int32, device=dev)[None, :] * 7
+        return (r.remainder_(2001) - 1000).to(torch.float32)
+
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    fwd = torch.full((tp - 1, M, W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(tp), dtype=torch.int32, device=dev)
+    p = t3.problem(M, N, K, tp, rank, *tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    order, own = oracle.chunk_order(tp, rank)
+    idx = torch.from_numpy(rows).to(dev)
+    t3.t3_track_reset(tp, track)
+    for unfused in (False, True):
+        print(f"unfused={unfused}", flush=True)
+        R = fresh_R()
+        fwd.fill_(gpu.SENTINEL)
+        if unfused:
+            C = torch.empty((M, N), dtype=torch.float32, device=dev)
+            t3.t3_gemm(p, A, B, C)
+            t3.t3_rs_reduce(p, C, R, fwd, track)
+        else:
+            t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+        torch.cuda.synchronize()
+        tr = t3.read_track(track, tp)
+        assert np.all(tr["ready"] == 1) and tr["error"] == 0 and tr["queue_len"] == tp - 1
+        Rg = R.index_select(0, idx).cpu().numpy()
+        fg = fwd.index_select(1, idx).cpu().numpy()
+        for s_, c in enumerate(int(x) for x in order):
+            want = S[:, c * W:(c + 1) * W]
+            if c == own:
+                assert np.array_equal(Rg[:, c * W:(c + 1) * W], want)
+            else:
+                assert np.array_equal(fg[s_], want)
+                assert np.array_equal(Rg[:, c * W:(c + 1) * W], inc_rows[:, c * W:(c + 1) * W])
+        assert not bool((fwd == gpu.SENTINEL).all(dim=2).any())
+        del R
+        if unfused:
+            del C
+    too_big = t3.problem(M + 16, N, K, tp, rank, *tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    with pytest.raises(RuntimeError):
+        t3.t3_gemm_rs_fused(too_big, A, B, fwd, fwd, track)      # refused before any launch
+
+
 def test_graph_replays_match_eager(gpu, oracle):
     """The step bench.py times (tracker reset + fused call) captured in a HIP graph: every
     replay, with eager work and synchronisation in between, must reproduce the eager result."""
