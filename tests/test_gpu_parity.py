@@ -809,6 +809,47 @@ def test_largest_supported_buffers(gpu, oracle):
         t3.t3_gemm_rs_fused(too_big, A, B, fwd, fwd, track)      # refused before any launch
 
 
+def test_largest_supported_operand(gpu, oracle):
+    """A just below the documented 2^31-element limit (the kernels address A and B with 32-bit
+    offsets): M = 32768 rows of K = lda = 65528 (1023 K-slabs and a tail of 56).  Integer inputs,
+    A given by a formula; sampled rows bit for bit."""
+    import torch
+    M, N, K, tp, rank, tile = 32768, 256, 65528, 2, 0, (256, 128)
+    assert M * K < 2 ** 31 < (M + 8) * K
+    W = N // tp
+    b = wl.make_integer_inputs(8, N, K, seed=1800, amax=1)[1]
+    rows = np.array([0, 255, 256, 16384, 32767], dtype=np.int64)
+    a_rows = ((rows[:, None] * 7 + np.arange(K, dtype=np.int64)[None, :] * 13) % 3 - 1).astype(np.float32)
+    inc_rows = ((rows[:, None] * 5 + np.arange(N, dtype=np.int64)[None, :] * 3) % 201 - 100).astype(np.float32)
+    S = oracle.reduce_rows(oracle.gemm_rows(wl.f32_to_bf16_bits(a_rows), b), inc_rows, tp)
+    dev = torch.device("cuda:0")
+    am = torch.arange(M, dtype=torch.int32, device=dev)[:, None] * 7
+    am = (am + torch.arange(K, dtype=torch.int32, device=dev)[None, :] * 13).remainder_(3) - 1
+    A = am.to(torch.float32).to(torch.bfloat16)
+    del am
+    B = gpu.to_dev_bits(b)
+    r = torch.arange(M, dtype=torch.int32, device=dev)[:, None] * 5
+    R = ((r + torch.arange(N, dtype=torch.int32, device=dev)[None, :] * 3).remainder_(201) - 100).to(torch.float32)
+    fwd = torch.full((tp - 1, M, W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(tp), dtype=torch.int32, device=dev)
+    p = t3.problem(M, N, K, tp, rank, *tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    t3.t3_track_reset(tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+    tr = t3.read_track(track, tp)
+    assert np.all(tr["ready"] == 1) and tr["error"] == 0
+    order, own = oracle.chunk_order(tp, rank)
+    idx = torch.from_numpy(rows).to(dev)
+    Rg = R.index_select(0, idx).cpu().numpy()
+    fg = fwd.index_select(1, idx).cpu().numpy()
+    for s_, c in enumerate(int(x) for x in order):
+        got = Rg[:, c * W:(c + 1) * W] if c == own else fg[s_]
+        assert np.array_equal(got, S[:, c * W:(c + 1) * W])
+    with pytest.raises(RuntimeError):      # one step further is refused before any launch
+        t3.t3_gemm_rs_fused(t3.problem(M + 8, N, K, tp, rank, *tile, flags=t3.T3_FLAG_FWD_DIRECT),
+                            A, B, R, fwd, track)
+
+
 def test_graph_replays_match_eager(gpu, oracle):
     """The step bench.py times (tracker reset + fused call) captured in a HIP graph: every
     replay, with eager work and synchronisation in between, must reproduce the eager result."""
