@@ -175,8 +175,9 @@ __device__ inline int decode_block(const Plan &p, int b, Tile &tl, int &slot, in
 // Phase offsets at start-up.  All workgroups of the first wave of tiles start together and would
 // reach their reduction traffic (incoming tile in, sums out) together, an HBM-bound burst during
 // which no matrix core works.  The first `stagger_blocks` workgroups are put into
-// `stagger_groups` phase groups; group g starts g * stagger_ticks (100 MHz ticks) late.  Later
-// workgroups are dispatched as earlier ones retire, so the offsets persist through the launch.
+// `stagger_groups` phase groups; group g starts g * stagger_ticks (100 MHz ticks) late.  A
+// persistent workgroup keeps its offset through all its tiles (every tile takes the same time);
+// with one workgroup per grid position, later ones are dispatched as earlier ones retire.
 __device__ inline void stagger_start(const Plan &p) {
   const int b = blockIdx.x;
   if (b >= p.stagger_blocks) return;
