@@ -18,7 +18,8 @@
  *
  * Conventions for every entry point
  *  - Pointers named A, B, C, R, fwd, track are DEVICE pointers owned by the caller.
- *    The library allocates and frees nothing and keeps no mutable global state.
+ *    The library allocates and frees nothing.  The only state it keeps is read-only after first
+ *    use: the compute-unit and XCD counts of each device it has launched on, and T3_STAGGER.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *    asynchronous on that stream and never synchronise it.
  *  - Arguments are validated on the host before anything is enqueued; on any status
@@ -121,8 +122,10 @@ typedef struct {
  * workgroups (as many as the device holds at once) that walk the grid positions in issue
  * order.  The first wave of workgroups starts in a few phase groups a few microseconds
  * apart, so that the compute units do not all reach their reduction traffic at the same
- * moment; the environment variable T3_STAGGER="groups,window_ns" overrides the default
- * (4 groups over 12 us), T3_STAGGER=0 turns it off.  Results do not depend on it.
+ * moment; the environment variable T3_STAGGER="groups,window_ns" (read once, at the first
+ * launch of the process) overrides the default (4 groups over 12 us), T3_STAGGER=0 turns it
+ * off.  Results do not depend on it.  The number of persistent workgroups follows the
+ * device's compute-unit count; the XCD grouping is applied on devices with 8 XCDs.
  *
  * Tracker state (Sec. 4.2): one caller-owned device array of t3_track_words(tp) uint32
  * words, cleared once by t3_track_reset().  It holds two banks of 3*tp + 2 words
@@ -143,15 +146,29 @@ typedef struct {
  * With a tile range, counters count the tiles of the range, and a chunk becomes ready (and
  * is released) only if all of its tiles lie in the range.
  * Counter, ready and queue-as-a-set are deterministic; the order of queue entries follows
- * the order in which chunks actually completed on the device.  A tile's results are visible
- * to the whole device before it is counted, so a consumer that observes ready[c] (with an
- * acquiring load) may read chunk c.
+ * the order in which chunks actually completed on the device.
+ * Publication: ready[c] is THE flag.  A tile's results are written with device-scope
+ * write-through stores and are acknowledged before the tile is counted; the count that
+ * completes a chunk writes its queue entry and then sets ready[c] with a device-scope release
+ * store.  A consumer on the same device that observes ready[c] == 1 with an acquiring load may
+ * read chunk c and will find c in the queue.  queue_len by itself publishes nothing: it is
+ * reserved before the entry is written and may run ahead of it.  (This is the ordering gfx950
+ * gives agent-scope stores and atomics; it is not promised to other devices or to the host
+ * before the launch has completed.)
+ * A release workgroup that gives up waiting (see `error`) leaves its slot unfilled although
+ * the call returned T3_OK: callers that use the default release mode check `error` (it stays 0
+ * in any launch that runs to completion).
  */
 
-/* Ring order of `rank` and the chunk it keeps.  Host pointers: order[tp], own[1]. */
+/* Ring order of `rank` and the chunk it keeps: order[s] = (rank + s) mod tp is the chunk produced
+   at ring step s (the staggered stage order of Sec. 4.4: GPU-0 runs stage 1 while GPU-1 runs stage
+   2), own = (rank - 1) mod tp the one produced last and kept (Sec. 4.1, Sec. 4.4).
+   Host pointers: order[tp], own[1].  T3_ERR_BAD_SHAPE unless 0 <= rank < tp. */
 t3_status t3_chunk_order(int32_t tp, int32_t rank, int32_t *order, int32_t *own);
 
-/* Tile shape the library would pick for this shape.  Host pointers. */
+/* Tile shape the library would pick for this shape: the tracked region of Sec. 4.2.1 (there a
+   wavefront's tile, here a workgroup's), chosen among the supported shapes for least padded
+   work, fastest main loop and a full device (an MI355X's 256 compute units).  Host pointers. */
 t3_status t3_default_tile(const t3_problem *p, int32_t *tile_m, int32_t *tile_n);
 
 /* Tiles per chunk for the problem's (or the default) tile shape.  Host pointer. */
@@ -165,8 +182,10 @@ t3_status t3_tile_of(const t3_problem *p, int64_t t, int32_t *s, int32_t *c, int
 /* Number of uint32 words of tracker state for a ring of size tp (0 if tp < 1). */
 int64_t t3_track_words(int32_t tp);
 
-/* Clears the tracker state (a small fill kernel on `stream`).  Needed once before the first
-   launch that uses `track`, not between launches.  track: device. */
+/* Clears the tracker state (a small fill kernel on `stream`): the set-up of the tracker's
+   entries before a producer kernel runs (Sec. 4.2.1, Sec. 4.4).  Needed once before the first
+   launch that uses `track`, not between launches.  track: device.  T3_ERR_BAD_SHAPE unless
+   1 <= tp <= 2^20. */
 t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
 
 /*

@@ -7,6 +7,8 @@
 #include <stdlib.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "t3_kernels.hip"
 
 namespace {
@@ -19,9 +21,77 @@ struct TileShape {
 // preference order of t3_default_tile
 constexpr TileShape kTileShapes[] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};
 constexpr int kNumTileShapes = sizeof(kTileShapes) / sizeof(kTileShapes[0]);
-constexpr int kNumXcd = 8;
+constexpr int kNumXcd = 8;            // the XCD grouping of decode_tile is written for 8 XCDs
+constexpr int kDefaultCus = 256;       // compute units of an MI355X (host-only plan queries assume it)
+constexpr int kMaxDevices = 64;
+// Matrix rate of one compute unit the start-up offsets are sized with: 4096 flop/clock at a
+// sustained ~1.5 GHz under load, in flop per nanosecond.
+constexpr double kCuFlopPerNs = 6.25e3;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// What the launch plan needs to know of the device it launches on, read from the runtime once
+// per device (hardware attributes only; they never change while the process lives).
+struct DeviceFacts {
+  int cus;     // compute units: persistent workgroups are sized to them
+  int xcds;    // accelerator dies the dispatcher deals workgroups to, round-robin
+};
+std::mutex g_facts_mutex;
+DeviceFacts g_facts[kMaxDevices];
+bool g_facts_known[kMaxDevices];
+
+// Facts of the current device; T3_ERR_HIP if the runtime cannot tell.
+t3_status device_facts(DeviceFacts *out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+  if (e == hipSuccess) {
+    std::lock_guard<std::mutex> lock(g_facts_mutex);
+    if (!g_facts_known[dev]) {
+      DeviceFacts f{0, 0};
+      e = hipDeviceGetAttribute(&f.cus, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e == hipSuccess && hipDeviceGetAttribute(&f.xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        f.xcds = 1;                // unknown: plan without XCD grouping
+      }
+      if (e == hipSuccess && f.cus < 1) e = hipErrorInvalidDevice;
+      if (e == hipSuccess) {
+        g_facts[dev] = f;
+        g_facts_known[dev] = true;
+      }
+    }
+    if (e == hipSuccess) *out = g_facts[dev];
+  }
+  if (e != hipSuccess) {
+    g_last_hip_error = (int32_t)e;
+    return T3_ERR_HIP;
+  }
+  return T3_OK;
+}
+
+// T3_STAGGER="groups,window_ns" from the environment, read once per process.
+struct StaggerEnv {
+  bool set = false, off = false;
+  int groups = 0, window_ns = 0;
+};
+const StaggerEnv &stagger_env() {
+  static const StaggerEnv env = [] {
+    StaggerEnv v;
+    if (const char *e = getenv("T3_STAGGER")) {
+      int eg = 0, ens = 0;
+      const int n = sscanf(e, "%d,%d", &eg, &ens);
+      if (n == 2 && eg > 1 && ens > 0) {
+        v.set = true;
+        v.groups = eg;
+        v.window_ns = ens;
+      } else if (n >= 1 && eg == 0) {
+        v.set = v.off = true;
+      }
+    }
+    return v;
+  }();
+  return env;
+}
 
 t3_status check_shape(const t3_problem *p) {
   if (!p) return T3_ERR_NULL;
@@ -37,10 +107,10 @@ bool tile_supported(int32_t tm, int32_t tn) {
   return false;
 }
 
-void default_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
+void default_tile(const t3_problem *p, int cus, int32_t *tm, int32_t *tn) {
   // Cheapest shape by (work padded up to whole tiles) x (how much slower than the 256 x 256
   // tile the shape's main loop runs per flop) x (how far the tiles fall short of filling the
-  // chip's 256 compute units).
+  // chip's `cus` compute units).
   static const double kSlower[kNumTileShapes] = {1.0, 1.28, 1.28, 1.45};
   const int64_t W = p->N / p->tp;
   double best = -1.0;
@@ -52,7 +122,7 @@ void default_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
     if (T == 0) continue;
     const double padded = (double)(Mt * kTileShapes[i].m) * (double)(Wt * kTileShapes[i].n) /
                           ((double)p->M * (double)W);
-    const double score = padded * kSlower[i] * (T < 256 ? 256.0 / (double)T : 1.0);
+    const double score = padded * kSlower[i] * (T < cus ? (double)cus / (double)T : 1.0);
     if (best < 0 || score < best) {
       best = score;
       *tm = kTileShapes[i].m;
@@ -63,7 +133,7 @@ void default_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
 
 t3_status resolve_tile(const t3_problem *p, int32_t *tm, int32_t *tn) {
   if (p->tile_m == 0 && p->tile_n == 0) {
-    default_tile(p, tm, tn);
+    default_tile(p, kDefaultCus, tm, tn);
     return T3_OK;
   }
   if (!tile_supported(p->tile_m, p->tile_n)) return T3_ERR_BAD_TILE;
@@ -151,6 +221,19 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   if (T >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
   *empty = (T == 0);
 
+  // (the last refusals, before the device is asked anything: with release workgroups and with
+  // split-K the grid still has to fit 31 bits)
+  const int64_t n_agents = (fused_like && !direct && !two_writers && p->tp > 1) ? T3_AGENTS : 0;
+  if (T + n_agents * (p->tp - 1) >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
+  if (two_writers && T * split_k >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
+  if ((need & kNeedTwoWriters) && (need & kNeedC) && p->upstream_agents < 0) return T3_ERR_BAD_SHAPE;
+
+  DeviceFacts dev{kDefaultCus, kNumXcd};
+  if (!*empty) {                                 // (nothing is launched otherwise: no device needed)
+    st = device_facts(&dev);
+    if (st != T3_OK) return st;
+  }
+
   t3k::Plan &q = *plan;
   q.A = static_cast<const uint16_t *>(A);
   q.B = static_cast<const uint16_t *>(B);
@@ -178,11 +261,12 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.flags = fused_like ? p->flags : 0u;
 
   // XCD grouping: split a stage's Mt x Wt tiles into 8 equal blocks, one per XCD, choosing the
-  // split whose block touches the fewest A rows + B columns.
+  // split whose block touches the fewest A rows + B columns.  (A device with another number of
+  // XCDs runs without grouping: plain issue order inside a stage.)
   q.xcd_nbm = 0;
   q.xcd_bmk = q.xcd_bnk = 0;
   int64_t best = -1;
-  for (int nbm = 1; nbm <= kNumXcd; nbm *= 2) {
+  for (int nbm = 1; nbm <= kNumXcd && dev.xcds == kNumXcd; nbm *= 2) {
     const int nbn = kNumXcd / nbm;
     if (Mt % nbm || Wt % nbn) continue;
     const int64_t foot = (Mt / nbm) * *tm + (Wt / nbn) * *tn;
@@ -197,12 +281,12 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // Release workgroups (default release mode only): `agents` per forwarded chunk, placed in
   // the grid `lag` stages after the chunk's own tiles, far enough that those tiles have been
   // dispatched and are mostly finished when the release workgroups start.
-  q.agents = (fused_like && !direct && !two_writers && p->tp > 1) ? T3_AGENTS : 0;
-  const int64_t resident = (*tm == 128 && *tn == 128) ? 512 : 256;   // tile workgroups the chip holds
+  q.agents = (int32_t)n_agents;
+  // tile workgroups the device holds at once: one per compute unit, two of the smallest tile
+  const int64_t resident = (int64_t)dev.cus * ((*tm == 128 && *tn == 128) ? 2 : 1);
   q.lag = (int32_t)(ceil_div(resident, tpc > 0 ? tpc : 1) + 1);
   if (q.lag > p->tp) q.lag = p->tp;
   q.rows_per_agent = q.agents ? (int32_t)ceil_div(p->M, q.agents) : 0;
-  if ((T + (int64_t)q.agents * (p->tp - 1)) >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
   // Start-up phase offsets (see stagger_start): four groups over a 12 us window, or half an
   // estimated tile time if that is shorter, once there are tiles enough to fill the chip.
   // The environment variable T3_STAGGER="groups,window_ns" overrides this ("0" turns it off).
@@ -210,18 +294,13 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   {
     int g = 4;
     double window_ns = 12000.0;
-    const double tile_ns = 2.0 * *tm * *tn * (double)p->K / 6.25e3;   // at ~6.25 TFLOP/s per compute unit
+    const double tile_ns = 2.0 * *tm * *tn * (double)p->K / kCuFlopPerNs;
     if (window_ns > tile_ns / 2) window_ns = tile_ns / 2;
     if (T < resident) g = 0;
-    if (const char *e = getenv("T3_STAGGER")) {
-      int eg = 0, ens = 0;
-      const int n = sscanf(e, "%d,%d", &eg, &ens);
-      if (n == 2 && eg > 1 && ens > 0) {
-        g = eg;
-        window_ns = ens;
-      } else if (n >= 1 && eg == 0) {
-        g = 0;
-      }
+    const StaggerEnv &env = stagger_env();
+    if (env.set) {
+      g = env.off ? 0 : env.groups;
+      if (!env.off) window_ns = env.window_ns;
     }
     if (g > 1 && window_ns >= 100.0) {
       q.stagger_groups = g;
@@ -247,15 +326,18 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
     q.upd_first = split_k + (step0 ? 0 : 1);
     const int64_t up_begin = (step0 && q.begin < tpc) ? (tpc < q.limit ? tpc : q.limit) : q.begin;
     q.expected_done = (int32_t)((q.limit - q.begin) * split_k + (q.limit - up_begin));
-    if (T * split_k >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
   }
   q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
   q.resident = (int32_t)resident;
   return T3_OK;
 }
 
-t3_status launched(void) {
-  const hipError_t e = hipGetLastError();
+// Launches `kernel` and returns what THIS launch returned: an error some earlier call left in
+// the runtime is not taken for ours.
+template <typename... KArgs>
+t3_status launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s, KArgs... a) {
+  void *args[] = {static_cast<void *>(&a)...};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, args, 0, s);
   if (e != hipSuccess) {
     g_last_hip_error = (int32_t)e;
     return T3_ERR_HIP;
@@ -266,7 +348,7 @@ t3_status launched(void) {
 inline unsigned grid_size(const t3k::Plan &q) { return (unsigned)q.total_blocks; }
 
 template <int MODE, int BKN>
-void launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
+t3_status launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
   // Persistent workgroups: as many as the chip holds at once, each walking the grid positions.
   // With release work in the grid (default release mode) every position gets a workgroup of
   // its own instead: a release position may have to wait for its chunk, and a persistent
@@ -278,19 +360,17 @@ void launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t 
   // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
   // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.
   if (tm == 256 && tn == 256)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE, BKN>), grid, dim3(512), 0, s, q);
+    return launch(t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE, BKN>, grid, dim3(512), s, q);
   else if (tm == 256 && tn == 128)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, BKN>), grid, dim3(512), 0, s, q);
+    return launch(t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, BKN>, grid, dim3(512), s, q);
   else if (tm == 128 && tn == 256)
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE, BKN>), grid, dim3(512), 0, s, q);
-  else
-    hipLaunchKernelGGL((t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE, BKN>), grid, dim3(256), 0, s, q);
+    return launch(t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE, BKN>, grid, dim3(512), s, q);
+  return launch(t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE, BKN>, grid, dim3(256), s, q);
 }
 
 template <int MODE>
-void launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, bool b_kn, hipStream_t s) {
-  if (b_kn) launch_gemm_layout<MODE, 1>(q, tm, tn, s);
-  else launch_gemm_layout<MODE, 0>(q, tm, tn, s);
+t3_status launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, bool b_kn, hipStream_t s) {
+  return b_kn ? launch_gemm_layout<MODE, 1>(q, tm, tn, s) : launch_gemm_layout<MODE, 0>(q, tm, tn, s);
 }
 
 }  // namespace
@@ -324,7 +404,7 @@ t3_status t3_default_tile(const t3_problem *p, int32_t *tile_m, int32_t *tile_n)
   if (!tile_m || !tile_n) return T3_ERR_NULL;
   const t3_status st = check_shape(p);
   if (st != T3_OK) return st;
-  default_tile(p, tile_m, tile_n);
+  default_tile(p, kDefaultCus, tile_m, tile_n);
   return T3_OK;
 }
 
@@ -362,9 +442,8 @@ int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 2 * (3ll * tp + 2) + 2;
 t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream) {
   if (!track) return T3_ERR_NULL;
   if (tp < 1 || tp > (1 << 20)) return T3_ERR_BAD_SHAPE;
-  hipLaunchKernelGGL(t3k::track_reset_kernel, dim3(1), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), track, (int)tp);
-  return launched();
+  return launch(t3k::track_reset_kernel, dim3(1), dim3(256), static_cast<hipStream_t>(stream), track,
+                (int)tp);
 }
 
 t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, float *R,
@@ -376,8 +455,8 @@ t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, fl
                                  fwd, track, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
-  launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN, static_cast<hipStream_t>(stream));
-  return launched();
+  return launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN,
+                                      static_cast<hipStream_t>(stream));
 }
 
 t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, void *stream) {
@@ -390,8 +469,8 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
   q.R = C;   // the GEMM kernel's output pointer, addressed with ldc
-  launch_gemm<t3k::kModeGemm>(q, tm, tn, p->b_layout == T3_B_KN, static_cast<hipStream_t>(stream));
-  return launched();
+  return launch_gemm<t3k::kModeGemm>(q, tm, tn, p->b_layout == T3_B_KN,
+                                     static_cast<hipStream_t>(stream));
 }
 
 t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, void *fwd,
@@ -406,14 +485,12 @@ t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, void *fwd,
   const dim3 grid(grid_size(q)), block(t3k::kThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (tm == 256 && tn == 256)
-    hipLaunchKernelGGL((t3k::reduce_tile_kernel<256, 256>), grid, block, 0, s, q);
+    return launch(t3k::reduce_tile_kernel<256, 256>, grid, block, s, q);
   else if (tm == 256 && tn == 128)
-    hipLaunchKernelGGL((t3k::reduce_tile_kernel<256, 128>), grid, block, 0, s, q);
+    return launch(t3k::reduce_tile_kernel<256, 128>, grid, block, s, q);
   else if (tm == 128 && tn == 256)
-    hipLaunchKernelGGL((t3k::reduce_tile_kernel<128, 256>), grid, block, 0, s, q);
-  else
-    hipLaunchKernelGGL((t3k::reduce_tile_kernel<128, 128>), grid, block, 0, s, q);
-  return launched();
+    return launch(t3k::reduce_tile_kernel<128, 256>, grid, block, s, q);
+  return launch(t3k::reduce_tile_kernel<128, 128>, grid, block, s, q);
 }
 
 t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *R,
@@ -425,21 +502,18 @@ t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *
                                  incoming, R, nullptr, track, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
-  if (p->upstream_agents < 0) return T3_ERR_BAD_SHAPE;
   unsigned blocks = grid_size(q);
   if (p->upstream_agents > 0 && (unsigned)p->upstream_agents < blocks)
     blocks = (unsigned)p->upstream_agents;     // the rest of the positions are walked in a loop
   const dim3 grid(blocks), block(t3k::kThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (tm == 256 && tn == 256)
-    hipLaunchKernelGGL((t3k::upstream_update_kernel<256, 256>), grid, block, 0, s, q);
+    return launch(t3k::upstream_update_kernel<256, 256>, grid, block, s, q);
   else if (tm == 256 && tn == 128)
-    hipLaunchKernelGGL((t3k::upstream_update_kernel<256, 128>), grid, block, 0, s, q);
+    return launch(t3k::upstream_update_kernel<256, 128>, grid, block, s, q);
   else if (tm == 128 && tn == 256)
-    hipLaunchKernelGGL((t3k::upstream_update_kernel<128, 256>), grid, block, 0, s, q);
-  else
-    hipLaunchKernelGGL((t3k::upstream_update_kernel<128, 128>), grid, block, 0, s, q);
-  return launched();
+    return launch(t3k::upstream_update_kernel<128, 256>, grid, block, s, q);
+  return launch(t3k::upstream_update_kernel<128, 128>, grid, block, s, q);
 }
 
 t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
@@ -454,9 +528,8 @@ t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
   if (p->tp < 2 || p->M == 0 || p->N == 0) return T3_OK;
   q.agents = T3_AGENTS;
   q.rows_per_agent = (int32_t)ceil_div(p->M, q.agents);
-  hipLaunchKernelGGL(t3k::release_ready_kernel, dim3((unsigned)(q.agents * (p->tp - 1))),
-                     dim3(t3k::kThreads), 0, static_cast<hipStream_t>(stream), q);
-  return launched();
+  return launch(t3k::release_ready_kernel, dim3((unsigned)(q.agents * (p->tp - 1))),
+                dim3(t3k::kThreads), static_cast<hipStream_t>(stream), q);
 }
 
 }  // extern "C"

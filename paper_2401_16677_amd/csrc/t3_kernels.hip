@@ -294,7 +294,10 @@ __device__ inline void track_count(const Plan &p, const Trk &t, int c) {
                                                     __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&t.queue[pos], (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      __hip_atomic_store(&t.ready[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // The flag is what publishes: a release store, so the queue entry above and everything this
+      // workgroup made visible before the barrier that precedes the count are ordered before it.
+      // (queue_len alone publishes nothing: it may run ahead of the entry it reserves.)
+      __hip_atomic_store(&t.ready[c], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
     trk_close_if_last(p, t, d);
   }
@@ -491,6 +494,11 @@ void gemm_tile_kernel(const Plan p) {
   // Waits for them are therefore explicit (s_waitcnt below).  Copies [q0, q1) of the slab's
   // NA + NB are issued by one call, so that a slab's copies can be spread over its micro-steps
   // (all eight wavefronts issuing all of theirs at once stalls them on the memory pipeline).
+  // They write m0 (the LDS destination of the copy) and say so in their clobber lists, so the
+  // compiler never assumes a value of its own survives them; it flags every clobber of that
+  // register as "reserved", which is exactly what is meant here.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
   auto issue_copies = [&](int kt, int stage, int q0, int q1) {
     const char *a = Ap + (int64_t)kt * (kBK * 2);
@@ -502,15 +510,16 @@ void gemm_tile_kernel(const Plan p) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
                      : "s"(dst + ldsA_w + q * 1024), "v"(offA[q]), "s"(a)
-                     : "memory");
+                     : "memory", "m0");
 #pragma unroll
     for (int q = 0; q < NB; ++q)
       if (NA + q >= q0 && NA + q < q1)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
                      : "s"(dst + ldsB_w + q * 1024), "v"(offB[q]), "s"(b)
-                     : "memory");
+                     : "memory", "m0");
   };
+#pragma clang diagnostic pop
   auto issue_slab = [&](int kt, int stage) { issue_copies(kt, stage, 0, NL); };
 
   // ---- MFMA operand addressing (v_mfma_f32_16x16x32_bf16): lane reads row (lane & 15) of a
