@@ -35,8 +35,13 @@ def test_algorithmic_bytes_closed_forms():
     assert b.algorithmic_bytes(w, False) == direct + 8 * fwd_elems     # copy: read + write again
     assert b.algorithmic_bytes(w, True, True) == direct - 2 * fwd_elems   # 2-byte forward slots
     assert abs(b.PEAK_BF16_TFLOPS - 256 * 2.4e9 * 4096 / 1e12) < 0.1 and b.PEAK_HBM_GBS == 8000.0
-    # the measured-traffic table only names workloads that exist
-    assert all(k[0] in wl.WORKLOADS and k[1] in ("direct", "copy") for k in b.MEASURED_TRAFFIC_BYTES)
+    # the transcribed-traffic table only names workloads that exist, and says where it is from
+    assert all(k[0] in wl.WORKLOADS and k[1] in ("direct", "copy") for k in b.PROFILED_TRAFFIC_BYTES)
+    assert "profiles/" in b.PROFILED_TRAFFIC_SOURCE and "transcribed" in b.PROFILED_TRAFFIC_SOURCE
+    # the headline is the largest configuration; every configuration gets a record
+    assert b.HEADLINE == "wide_fc2" and set(b.CONFIGS) == {
+        "tiny_outproj", "gpt3_outproj", "gpt3_fc2", "wide_fc2", "hightp_outproj"}
+    assert max(b.CONFIGS, key=lambda n: wl.WORKLOADS[n].flop) == b.HEADLINE
 
 
 def test_named_configurations_have_the_stated_shapes():

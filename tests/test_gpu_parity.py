@@ -561,25 +561,29 @@ def test_integer_state_repeats(gpu, oracle):
 
 
 # ---------------------------------------------------------------- full-size configurations
-# The launch configuration bench.py times, checked on sampled rows the oracle computes one by
-# one (all N columns of each sampled row: every chunk, every tile column; rows drawn from
-# every tile row plus the first and last row), and on properties that hold at any size.
+# The launch configuration bench.py times, every element against the oracle (the full fp64
+# GEMM + reduction takes the host cores a few seconds per configuration; it is computed once
+# per workload and shared by the two release modes).
 FULL = ["gpt3_outproj", "gpt3_fc2", "wide_fc2", "hightp_outproj"]
+_full_cache = {}
+
+
+def _full_oracle(oracle, name):
+    if name not in _full_cache:
+        _full_cache.clear()                       # one workload's arrays at a time
+        w = wl.WORKLOADS[name]
+        a, b, inc = wl.make_inputs(w)
+        _full_cache[name] = (a, b, inc, oracle.reduce_rows(oracle.gemm_rows(a, b), inc, w.tp))
+    return _full_cache[name]
 
 
 @pytest.mark.parametrize("direct", [True, False])
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_sampled_rows(gpu, oracle, name, direct):
+def test_full_size_every_element(gpu, oracle, name, direct):
     import torch
     w = wl.WORKLOADS[name]
     print(f"workload={name} direct={direct} tile={w.tile_m}x{w.tile_n}", flush=True)
-    a, b, inc = wl.make_inputs(w)
-    rng = np.random.default_rng(w.seed)
-    Mt = -(-w.M // w.tile_m)
-    rows = sorted({0, w.M - 1} | {int(mi * w.tile_m + rng.integers(0, min(w.tile_m, w.M - mi * w.tile_m)))
-                                  for mi in range(Mt)})
-    rows = np.array(rows, dtype=np.int32)
-    S = oracle.reduce_rows(oracle.gemm_rows(a, b, rows=rows), inc, w.tp, rows=rows)   # (nrows, N)
+    a, b, inc, S = _full_oracle(oracle, name)     # S: (M, N) fp32 sums
 
     dev = torch.device("cuda:0")
     A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
@@ -599,26 +603,27 @@ def test_full_size_sampled_rows(gpu, oracle, name, direct):
     assert tr["queue_len"] == w.tp - 1 and tr["error"] == 0 and tr["gen"] == 1
     assert sorted(tr["queue"][:w.tp - 1].tolist()) == sorted(c for c in range(w.tp) if c != own)
 
-    idx = torch.from_numpy(rows.astype(np.int64)).to(dev)
-    Rg = R.index_select(0, idx).cpu().numpy()
-    fg = fwd.index_select(1, idx).cpu().numpy()
+    Rg = R.cpu().numpy()
+    fg = fwd.cpu().numpy()
     W = w.W
-    errs = []
+    scale = float(np.abs(S).max())
+    errs, worst = [], 0.0
     for s in range(w.tp):
         c = int(order[s])
-        want = S[:, c * W:(c + 1) * W]
-        if c == own:
-            errs.append(gpu.rel_err(Rg[:, c * W:(c + 1) * W], want))
-        else:
-            errs.append(gpu.rel_err(fg[s], want))
+        cols = slice(c * W, (c + 1) * W)
+        want = S[:, cols]
+        got = Rg[:, cols] if c == own else fg[s]
+        errs.append(gpu.rel_err(got, want))
+        worst = max(worst, float(np.abs(got.astype(np.float64) - want).max()))
+        if c != own:
             if direct:      # R keeps the incoming data on forwarded chunks
-                assert np.array_equal(Rg[:, c * W:(c + 1) * W], inc[rows][:, c * W:(c + 1) * W])
+                assert np.array_equal(Rg[:, cols], inc[:, cols])
             else:           # the slot is a copy of what was reduced in place
-                assert np.array_equal(Rg[:, c * W:(c + 1) * W], fg[s])
-    print(f"max normwise error over chunks {max(errs):.3e}", flush=True)
+                assert np.array_equal(Rg[:, cols], fg[s])
+    print(f"max normwise error over chunks {max(errs):.3e}; max |diff| over all {w.M * w.N} "
+          f"elements {worst:.3e} = {worst / scale:.2e} of the largest sum", flush=True)
     assert max(errs) <= TOL and max(errs) <= EXPECT
-    # any-size properties: nothing but finite values, and no forward slot left untouched
-    assert bool(torch.isfinite(fwd).all()) and not bool((fwd == gpu.SENTINEL).all(dim=2).any())
+    assert worst <= 1e-4 * scale                  # element by element: no tile, row or block is off
 
 
 @pytest.mark.parametrize("name", sorted(wl.PAPER_SHAPES))

@@ -1,0 +1,148 @@
+"""GPU parity of the launch shape the benchmark times: persistent workgroups that each walk
+three or more tiles (LDS reused from tile to tile, the count of a tile deferred into the next
+tile's main loop), every element compared with the CPU oracle.
+
+Small-integer inputs make fp32 accumulation exact in any order, so R, the forward slots and C
+must equal the fp64 oracle bit for bit; the shapes have at least three tiles per resident
+workgroup for each of the four tile shapes (256 compute units hold 256 workgroups, 512 of the
+128 x 128 tile), a ragged last tile row and a K that ends in a partial slab."""
+import numpy as np
+import pytest
+
+from paper_2401_16677_amd import binding as t3
+from paper_2401_16677_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+CUS = 256      # compute units of the device these shapes are sized for
+
+# M, N, K, tp, rank, tile: tiles = ceil(M/tm) * ceil(N/tp/tn) * tp
+MULTI = {
+    (256, 256): (4090, 12288, 136, 8, 3),     # 16 x 6 x 8 = 768 tiles = 3 per workgroup
+    (256, 128): (4090, 8192, 136, 8, 5),      # 16 x 8 x 8 = 1024 = 4
+    (128, 256): (2040, 12288, 136, 8, 7),     # 16 x 6 x 8 = 768 = 3
+    (128, 128): (2040, 12288, 136, 8, 0),     # 16 x 12 x 8 = 1536 = 3 (two workgroups per unit)
+}
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "needs a GPU"
+    from tests import gpu_harness
+    return gpu_harness
+
+
+def _tiles_per_workgroup(M, N, tp, tile):
+    resident = CUS * (2 if tile == (128, 128) else 1)
+    return (-(-M // tile[0])) * (-(-(N // tp) // tile[1])) * tp / resident
+
+
+def _check_ints(got, want, own):
+    assert np.array_equal(got["counter"], want["counter"])
+    assert np.array_equal(got["ready"], want["ready"])
+    n = want["queue_len"]
+    assert got["queue_len"] == n
+    assert set(got["queue"][:n].tolist()) == set(want["queue"][:n].tolist())
+    assert len(set(got["queue"][:n].tolist())) == n and own not in got["queue"][:n]
+    assert np.all(got["queue"][n:] == 0xFFFFFFFF)
+    assert got["error"] == 0
+
+
+def _first_mismatch(got, want):
+    bad = np.argwhere(got != want)
+    return "equal" if bad.size == 0 else f"{bad.shape[0]} mismatches, first at {tuple(bad[0])}"
+
+
+@pytest.mark.parametrize("mode", ["fused_direct", "fused_copy", "unfused_direct", "fused_direct_step0"])
+@pytest.mark.parametrize("tile", sorted(MULTI))
+def test_three_tiles_per_workgroup_every_element(gpu, oracle, tile, mode):
+    M, N, K, tp, rank = MULTI[tile]
+    assert _tiles_per_workgroup(M, N, tp, tile) >= 3
+    direct = "direct" in mode
+    step0 = mode.endswith("step0")
+    print(f"tile={tile} shape={(M, N, K, tp, rank)} mode={mode}", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=900 + tile[0] + tile[1] // 2)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=direct, step0_store_only=step0,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    flags = (t3.T3_FLAG_FWD_DIRECT if direct else 0) | (t3.T3_FLAG_STEP0_STORE_ONLY if step0 else 0)
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=flags, unfused=mode.startswith("unfused"),
+                      ldr_pad=4, lda_pad=8)
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    assert np.all(got["R_pad"] == 123.0)
+    if mode.startswith("unfused"):
+        assert np.array_equal(got["C"], oracle.gemm_rows(a, b).astype(np.float32))
+    _check_ints(got, want, want["own"])
+
+
+@pytest.mark.parametrize("tile", [(256, 256), (128, 128)])
+def test_three_tiles_per_workgroup_b_stored_k_by_n(gpu, oracle, tile):
+    M, N, _, tp, rank = MULTI[tile]
+    K = 192                                   # whole slabs only in this layout
+    print(f"tile={tile} shape={(M, N, K, tp, rank)} B stored K x N", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=940 + tile[0])
+    want = oracle.fused_path(a, np.ascontiguousarray(b.T), inc, tp, rank, *tile, b_layout=oracle.B_KN,
+                             fwd_direct=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT, b_kn=True, lda_pad=8)
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    _check_ints(got, want, want["own"])
+
+
+@pytest.mark.parametrize("direct", [True, False])
+@pytest.mark.parametrize("tile", [(256, 256), (256, 128)])
+def test_three_tiles_per_workgroup_bf16_slots(gpu, oracle, tile, direct):
+    M, N, K, tp, rank = MULTI[tile]
+    print(f"tile={tile} shape={(M, N, K, tp, rank)} bfloat16 forward slots direct={direct}", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=960 + tile[1])
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=direct, fwd_bf16=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL_BF16, np.uint16))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile,
+                      flags=t3.T3_FLAG_FWD_BF16 | (t3.T3_FLAG_FWD_DIRECT if direct else 0))
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    _check_ints(got, want, want["own"])
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("tile", [(256, 256), (128, 256)])
+def test_tile_range_cutting_a_persistent_wave(gpu, oracle, tile, unfused):
+    """A range of the issue order that starts inside the first wave of workgroups and ends inside
+    the third: workgroups find their first and last grid positions outside the range, chunks at
+    both ends stay incomplete."""
+    M, N, K, tp, rank = MULTI[tile]
+    tpc = oracle.tiles_per_chunk(M, N, tp, *tile)
+    begin, limit = 100, 2 * CUS + 77
+    assert 0 < begin < CUS and 2 * CUS < limit < 3 * CUS and limit % tpc and begin % tpc
+    print(f"tile={tile} range=[{begin},{limit}) of {tp * tpc} unfused={unfused}", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=980 + tile[0])
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, tile_begin=begin, tile_limit=limit,
+                             fwd_direct=True, fwd_init=sent)
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT, tile_begin=begin,
+                      tile_limit=limit, unfused=unfused)
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    _check_ints(got, want, want["own"])
+
+
+@pytest.mark.parametrize("tile", [(256, 256), (128, 128)])
+def test_three_tiles_per_workgroup_float_every_element(gpu, oracle, tile):
+    """The same launch shape on normally distributed inputs: every element within 1e-4 of the
+    largest sum (fp32 accumulation of K = 136 products), and the norm far inside the 5e-3 bound."""
+    M, N, K, tp, rank = MULTI[tile]
+    w = wl.make_shape("multi", M, N, K, tp, rank, *tile, index=70 + tile[0] // 128)
+    a, b, inc = wl.make_inputs(w)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    scale = float(np.abs(want["fwd"]).max())
+    for name in ("R", "fwd"):
+        d = np.abs(got[name].astype(np.float64) - want[name])
+        print(f"tile={tile} {name}: max |diff| {d.max():.3e} (scale {scale:.3e}), "
+              f"normwise {gpu.rel_err(got[name], want[name]):.3e}", flush=True)
+        assert d.max() <= 1e-4 * scale
+        assert gpu.rel_err(got[name], want[name]) <= 1e-5
+    _check_ints(got, want, want["own"])
