@@ -213,6 +213,30 @@ t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
 t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, float *R,
                            void *fwd, uint32_t *track, void *stream);
 
+/*
+ * t3_gemm_rs_fused for callers that cannot allocate device memory at all -- code under HIP
+ * graph capture, tight serving loops, harnesses that forbid it -- and so cannot supply the
+ * tracker state either: the same kernels, the same results in R and fwd, with the tracker
+ * state (the counters, flags and queue the kernels work in) held in a fixed array inside the
+ * library instead of a caller's.  The call allocates and frees nothing.
+ *
+ *   A, B, R, fwd, stream    as for t3_gemm_rs_fused
+ *   track_copy              NULL, or device memory of t3_track_words(tp) words that receives a
+ *                           copy of the tracker state as the launch left it (same layout:
+ *                           results in bank (gen - 1) & 1, gen == 1 after a launch that ran tiles)
+ *
+ * Limits: tp <= T3_STATIC_MAX_TP (T3_ERR_UNSUPPORTED beyond it); the array takes
+ * 2 * (3 * T3_STATIC_MAX_TP + 2) + 2 words (under 2 KiB) on every device the library has run
+ * on, until the process ends.  Every call clears it first (a small fill kernel on `stream`)
+ * and all calls on one device share it: calls that overlap on one device -- different
+ * streams, or graph replays in flight together -- race on it and must be serialised by the
+ * caller.  Two-writer mode needs a caller's tracker (its second call must find the first
+ * call's counts) and is refused here with T3_ERR_UNSUPPORTED.
+ */
+#define T3_STATIC_MAX_TP 64
+t3_status t3_gemm_rs_fused_static(const t3_problem *p, const void *A, const void *B, float *R,
+                                  void *fwd, uint32_t *track_copy, void *stream);
+
 /* Unfused baseline, step 1: the plain sliced GEMM (Sec. 2.4).  C fp32 [M][ldc] out.
    tp/rank/tile_limit order the tiles exactly as in the fused call; flags are ignored. */
 t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, void *stream);

@@ -18,10 +18,11 @@ T3_FLAG_STEP0_STORE_ONLY = 1
 T3_FLAG_FWD_DIRECT = 2
 T3_FLAG_TWO_WRITERS = 4
 T3_FLAG_FWD_BF16 = 8
+T3_STATIC_MAX_TP = 64
 
 EXPORTS = ["t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
            "t3_track_words", "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
-           "t3_upstream_update", "t3_release_chunks",
+           "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static",
            "t3_status_string", "t3_last_hip_error"]
 
 
@@ -68,6 +69,7 @@ def lib():
         L.t3_track_words.restype = i64
         L.t3_track_reset.argtypes = [i32, vp, vp]
         L.t3_gemm_rs_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp]
+        L.t3_gemm_rs_fused_static.argtypes = [pp, vp, vp, vp, vp, vp, vp]
         L.t3_gemm.argtypes = [pp, vp, vp, vp, vp]
         L.t3_rs_reduce.argtypes = [pp, vp, vp, vp, vp, vp]
         L.t3_upstream_update.argtypes = [pp, vp, vp, vp, vp]
@@ -77,7 +79,7 @@ def lib():
         L.t3_last_hip_error.restype = i32
         for f in ("t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
                   "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
-                  "t3_upstream_update", "t3_release_chunks"):
+                  "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -168,6 +170,12 @@ def t3_track_reset(tp, track, stream=None):
 def t3_gemm_rs_fused(p, A, B, R, fwd, track, stream=None):
     _check(lib().t3_gemm_rs_fused(ctypes.byref(p), _dptr(A), _dptr(B), _dptr(R), _dptr(fwd),
                                   _dptr(track), _stream(stream)), "t3_gemm_rs_fused")
+
+
+def t3_gemm_rs_fused_static(p, A, B, R, fwd, track_copy=None, stream=None):
+    _check(lib().t3_gemm_rs_fused_static(ctypes.byref(p), _dptr(A), _dptr(B), _dptr(R), _dptr(fwd),
+                                         _dptr(track_copy), _stream(stream)),
+           "t3_gemm_rs_fused_static")
 
 
 def t3_gemm(p, A, B, C, stream=None):

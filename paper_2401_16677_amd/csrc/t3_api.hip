@@ -69,6 +69,37 @@ t3_status device_facts(DeviceFacts *out) {
   return T3_OK;
 }
 
+// Tracker state for t3_gemm_rs_fused_static, the entry point for callers that cannot allocate:
+// one array per device (each GPU the library runs on holds its own copy at its own address
+// until the process ends).  Host code never uses the array's name as an address: the device
+// address is looked up once per device and kept.
+constexpr int kStaticMaxTp = T3_STATIC_MAX_TP;
+constexpr int kStaticTrackWords = 2 * (3 * kStaticMaxTp + 2) + 2;
+static __device__ __align__(256) uint32_t scratch[kStaticTrackWords];
+uint32_t *g_scratch_ptr[kMaxDevices];
+
+// Device address of the current device's `scratch`; T3_ERR_HIP if the runtime cannot tell.
+t3_status static_track(uint32_t **out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+  if (e == hipSuccess) {
+    std::lock_guard<std::mutex> lock(g_facts_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void *ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));   // the current device's copy
+      if (e == hipSuccess && !ptr) e = hipErrorInvalidSymbol;
+      if (e == hipSuccess) g_scratch_ptr[dev] = static_cast<uint32_t *>(ptr);
+    }
+    if (e == hipSuccess) *out = g_scratch_ptr[dev];
+  }
+  if (e != hipSuccess) {
+    g_last_hip_error = (int32_t)e;
+    return T3_ERR_HIP;
+  }
+  return T3_OK;
+}
+
 // T3_STAGGER="groups,window_ns" from the environment, read once per process.
 struct StaggerEnv {
   bool set = false, off = false;
@@ -457,6 +488,37 @@ t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, fl
   if (empty) return T3_OK;
   return launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN,
                                       static_cast<hipStream_t>(stream));
+}
+
+t3_status t3_gemm_rs_fused_static(const t3_problem *p, const void *A, const void *B, float *R,
+                                  void *fwd, uint32_t *track_copy, void *stream) {
+  if (!p) return T3_ERR_NULL;
+  if (p->tp > kStaticMaxTp) return T3_ERR_UNSUPPORTED;   // the static tracker state holds no more
+  if (p->flags & T3_FLAG_TWO_WRITERS) return T3_ERR_UNSUPPORTED;   // needs a tracker that outlives the call
+  // validate everything first (a non-null stand-in for the tracker pointer: nothing reads it)
+  t3k::Plan q;
+  int32_t tm, tn;
+  bool empty = false;
+  uint32_t stand_in = 0;
+  t3_status st = make_plan(p, kNeedAB | kNeedR | kNeedFwd | kNeedTrack, A, B, nullptr, R, fwd,
+                           &stand_in, &q, &tm, &tn, &empty);
+  if (st != T3_OK) return st;
+  uint32_t *track = nullptr;
+  st = static_track(&track);
+  if (st != T3_OK) return st;
+  q.track = track;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // the array keeps the last call's contents: every call starts from a cleared tracker
+  st = launch(t3k::track_reset_kernel, dim3(1), dim3(256), s, track, (int)p->tp);
+  if (st != T3_OK) return st;
+  if (!empty) {
+    st = launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN, s);
+    if (st != T3_OK) return st;
+  }
+  if (track_copy)
+    st = launch(t3k::track_copy_kernel, dim3(1), dim3(256), s, (const uint32_t *)track, track_copy,
+                (int)t3_track_words(p->tp));
+  return st;
 }
 
 t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, void *stream) {

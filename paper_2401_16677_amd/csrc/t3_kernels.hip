@@ -981,4 +981,10 @@ __global__ void track_reset_kernel(uint32_t *track, int P) {
   }
 }
 
+// Copies n words of tracker state (for callers that want to read the state another array holds).
+__global__ void track_copy_kernel(const uint32_t *src, uint32_t *dst, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x)
+    dst[i] = __hip_atomic_load(&src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 }  // namespace t3k
