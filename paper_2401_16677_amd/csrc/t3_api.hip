@@ -183,7 +183,9 @@ static_assert(sizeof(t3_problem) == 96, "layout documented in the header");
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 enum Need { kNeedAB = 1, kNeedR = 2, kNeedC = 4, kNeedFwd = 8, kNeedTrack = 16,
-            kNeedTwoWriters = 32 /* the call exists only in two-writer mode */ };
+            kNeedTwoWriters = 32 /* the call exists only in two-writer mode */,
+            kMayPair = 64 /* the call launches the tile kernel, which can compute 256 x 256
+                             workgroup tiles under 128 x 256 tracked ones */ };
 
 // Validates everything and fills the plan.  *empty is set when there is nothing to launch.
 t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B, const float *C,
@@ -247,9 +249,25 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // bfloat16 forward slots move 8 elements per 16-byte access
   if ((need & kNeedFwd) && fused_like && (p->flags & T3_FLAG_FWD_BF16) && W % 8) return T3_ERR_ALIGN;
 
-  const int64_t Mt = ceil_div(p->M, *tm), Wt = ceil_div(W, *tn);
+  // tracked tiles (the problem's tile shape): what the issue order, the tile range and the
+  // tracker's thresholds are counted in
+  const int64_t Mt_t = ceil_div(p->M, *tm), Wt = ceil_div(W, *tn);
+  const int64_t tpc_t = Mt_t * Wt, T_t = tpc_t * p->tp;
+  if (T_t >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
+  const int64_t limit_t = (p->tile_limit < 0 || p->tile_limit > T_t) ? T_t : p->tile_limit;
+  const int64_t begin_t = p->tile_begin < 0 ? 0 : (p->tile_begin > limit_t ? limit_t : p->tile_begin);
+  // Workgroup tiles.  128 x 256 tracked tiles are computed two at a time, as one 256 x 256
+  // workgroup tile (tracked tiles 2 mi and 2 mi + 1 of a tile column are neighbours in the issue
+  // order): the larger tile needs a third less operand traffic per product.  Only for ranges of
+  // whole ring steps, so that no pair is cut by the range, and not with two writers.
+  int64_t pair_m = 1;
+  if ((need & kMayPair) && *tm == 128 && *tn == 256 && !two_writers && tpc_t > 0 && Mt_t > 1 &&
+      begin_t % tpc_t == 0 && limit_t % tpc_t == 0) {
+    pair_m = 2;
+    *tm = 256;
+  }
+  const int64_t Mt = ceil_div(Mt_t, pair_m);
   const int64_t tpc = Mt * Wt, T = tpc * p->tp;
-  if (T >= (1ll << 31)) return T3_ERR_UNSUPPORTED;
   *empty = (T == 0);
 
   // (the last refusals, before the device is asked anything: with release workgroups and with
@@ -276,8 +294,8 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.ldb = p->ldb;
   q.ldr = p->ldr;
   q.ldc = p->ldc;
-  q.limit = (p->tile_limit < 0 || p->tile_limit > T) ? T : p->tile_limit;
-  q.begin = p->tile_begin < 0 ? 0 : (p->tile_begin > q.limit ? q.limit : p->tile_begin);
+  q.limit = limit_t;
+  q.begin = begin_t;
   if (q.begin >= q.limit) *empty = true;       // an empty tile range: nothing to launch
   q.M = p->M;
   q.N = p->N;
@@ -289,6 +307,9 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.Mt = (int32_t)Mt;
   q.Wt = (int32_t)Wt;
   q.tpc = (int32_t)tpc;
+  q.pair_m = (int32_t)pair_m;
+  q.Mt_t = (int32_t)Mt_t;
+  q.tpc_t = (int32_t)tpc_t;
   q.flags = fused_like ? p->flags : 0u;
 
   // XCD grouping: split a stage's Mt x Wt tiles into 8 equal blocks, one per XCD, choosing the
@@ -344,8 +365,10 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // chunks all of whose tiles lie in [begin, limit); the forwarded ones among them get released
   int64_t released = 0;
   for (int64_t s = 0; s + 1 < p->tp; ++s)
-    if (s * tpc >= q.begin && (s + 1) * tpc <= q.limit && tpc > 0) ++released;
-  q.expected_done = (int32_t)((q.limit - q.begin) + q.agents * released);
+    if (s * tpc_t >= q.begin && (s + 1) * tpc_t <= q.limit && tpc_t > 0) ++released;
+  // (paired tiles: the range is whole ring steps, tpc workgroup tiles each)
+  const int64_t wg_tiles = pair_m > 1 ? (q.limit - q.begin) / tpc_t * tpc : q.limit - q.begin;
+  q.expected_done = (int32_t)(wg_tiles + q.agents * released);
   // updates expected per element (Sec. 4.2.1): with two writers the launches of both count in
   // one bank, which closes when the tiles of both have been counted
   q.upd_first = q.upd_rest = 1;
@@ -358,6 +381,8 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
     const int64_t up_begin = (step0 && q.begin < tpc) ? (tpc < q.limit ? tpc : q.limit) : q.begin;
     q.expected_done = (int32_t)((q.limit - q.begin) * split_k + (q.limit - up_begin));
   }
+  // K walks start at a different slab on every XCD (see the kernels' `koff`)
+  q.k_groups = dev.xcds > 1 ? dev.xcds : 0;
   q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
   q.resident = (int32_t)resident;
   return T3_OK;
@@ -387,14 +412,24 @@ t3_status launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStre
   const bool persistent = q.agents == 0;
   const int64_t positions = (int64_t)q.total_blocks * (MODE == t3k::kModeFused ? q.split_k : 1);
   const dim3 grid((unsigned)(persistent && positions > q.resident ? q.resident : positions));
-  // K-slabs of 64 everywhere.  256 x 256: 8 wavefronts of 128 x 64, two 64-KiB stages; the
+  // K-slabs of 64 everywhere.  256 x 256: 4 wavefronts of 128 x 128 (or 8 of 128 x 64), two 64-KiB stages; the
   // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
   // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.
-  if (tm == 256 && tn == 256)
+  if (tm == 256 && tn == 256) {
+    // B stored N x K: four wavefronts of 128 x 128 with the hand-ordered main loop, which adds the
+    // incoming partial on the way out.  It has no two-writer epilogue and does not write
+    // bfloat16 forward slots itself: those, and B stored K x N, take the eight-wavefront kernel.
+    const bool eight = BKN || (MODE == t3k::kModeFused &&
+                               ((q.flags & t3k::kFlagTwoWriters) ||
+                                ((q.flags & t3k::kFlagFwdDirect) && (q.flags & t3k::kFlagFwdBf16))));
+    if constexpr (!BKN) {
+      if (!eight) return launch(t3k::gemm_tile_kernel<256, 256, 2, 2, 2, MODE, 0>, grid, dim3(256), s, q);
+    }
     return launch(t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE, BKN>, grid, dim3(512), s, q);
-  else if (tm == 256 && tn == 128)
+  }
+  if (tm == 256 && tn == 128)
     return launch(t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, BKN>, grid, dim3(512), s, q);
-  else if (tm == 128 && tn == 256)
+  if (tm == 128 && tn == 256)
     return launch(t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE, BKN>, grid, dim3(512), s, q);
   return launch(t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE, BKN>, grid, dim3(256), s, q);
 }
@@ -482,7 +517,7 @@ t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, fl
   t3k::Plan q;
   int32_t tm, tn;
   bool empty = false;
-  const t3_status st = make_plan(p, kNeedAB | kNeedR | kNeedFwd | kNeedTrack, A, B, nullptr, R,
+  const t3_status st = make_plan(p, kNeedAB | kNeedR | kNeedFwd | kNeedTrack | kMayPair, A, B, nullptr, R,
                                  fwd, track, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
@@ -500,7 +535,7 @@ t3_status t3_gemm_rs_fused_static(const t3_problem *p, const void *A, const void
   int32_t tm, tn;
   bool empty = false;
   uint32_t stand_in = 0;
-  t3_status st = make_plan(p, kNeedAB | kNeedR | kNeedFwd | kNeedTrack, A, B, nullptr, R, fwd,
+  t3_status st = make_plan(p, kNeedAB | kNeedR | kNeedFwd | kNeedTrack | kMayPair, A, B, nullptr, R, fwd,
                            &stand_in, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   uint32_t *track = nullptr;
@@ -526,7 +561,7 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
   t3k::Plan q;
   int32_t tm, tn;
   bool empty = false;
-  const t3_status st = make_plan(p, kNeedAB | kNeedC, A, B, C, nullptr, nullptr, nullptr, &q,
+  const t3_status st = make_plan(p, kNeedAB | kNeedC | kMayPair, A, B, C, nullptr, nullptr, nullptr, &q,
                                  &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;

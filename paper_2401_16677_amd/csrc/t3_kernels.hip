@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #ifndef T3_MH
 #define T3_MH 2            // row passes per MFMA k-step of a 128-row wavefront tile (2 or 4)
 #endif
@@ -62,7 +64,12 @@ struct Plan {
   int64_t limit;     // tiles with issue index >= limit do nothing
   int64_t begin;     // nor do tiles with issue index < begin
   int32_t M, N, K, P, rank, W, own;
-  int32_t Mt, Wt, tpc;
+  int32_t Mt, Wt, tpc;                 // the grid of WORKGROUP tiles: rows, columns, tiles per chunk
+  // The tracked tile may be half a workgroup tile high (128 x 256 tracked, 256 x 256 computed):
+  // then pair_m == 2, a workgroup tile covers the tracked tiles 2 mi and 2 mi + 1 of its column
+  // (consecutive in the issue order) and counts as many as exist.  Otherwise pair_m == 1 and
+  // the two grids are the same.
+  int32_t pair_m, Mt_t, tpc_t;         // tracked tile rows and tracked tiles per chunk
   int32_t xcd_nbm, xcd_bmk, xcd_bnk;   // XCD grouping of a stage's tiles; xcd_nbm == 0: none
   int32_t agents, lag, rows_per_agent; // release workgroups per chunk, their lag in stages
   int32_t expected_done;               // grid positions of this launch that do work
@@ -71,6 +78,7 @@ struct Plan {
   int32_t upd_first, upd_rest;         // updates expected per element of chunk order[0] / the others
   int32_t split_k;                     // >= 1: workgroups that share a tile, each taking a part of K (Sec. 7.7)
   int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
+  int32_t k_groups;                    // > 1: workgroup w starts its K loop (w % k_groups) / k_groups of the way in
   uint32_t flags;
 };
 
@@ -137,7 +145,8 @@ __device__ inline bool decode_tile(const Plan &p, int s, int j, Tile &tl) {
     mi = j % p.Mt;
     nj = j / p.Mt;
   }
-  const int64_t t = (int64_t)s * p.tpc + (int64_t)nj * p.Mt + mi;   // issue index
+  // issue index of the (first) tracked tile
+  const int64_t t = (int64_t)s * p.tpc_t + (int64_t)nj * p.Mt_t + (int64_t)mi * p.pair_m;
   int c = p.rank + s;
   if (c >= p.P) c -= p.P;
   tl.s = s;
@@ -272,23 +281,24 @@ __device__ inline void copy_chunk_rows(const Plan &p, int slot, int c, int r0, i
 // acknowledged (vmcnt == 0 in every wavefront, then the barrier) the tile is counted.  A
 // device-scope release fence instead would write back the whole L2 for every tile and costs
 // several times the reduction itself.
-__device__ inline void track_count(const Plan &p, const Trk &t, int c);
-__device__ inline void track_tile(const Plan &p, const Trk &t, int c) {
+__device__ inline void track_count(const Plan &p, const Trk &t, int c, int n = 1);
+__device__ inline void track_tile(const Plan &p, const Trk &t, int c, int n = 1) {
   __builtin_amdgcn_s_waitcnt(kWaitAll);
   __syncthreads();
-  track_count(p, t, c);
+  track_count(p, t, c, n);
 }
 // The counting itself, once every wavefront's stores of the tile are known to be acknowledged
 // and a barrier has passed.
-__device__ inline void track_count(const Plan &p, const Trk &t, int c) {
+// (n: tracked tiles the workgroup's tile covers)
+__device__ inline void track_count(const Plan &p, const Trk &t, int c, int n) {
   if (threadIdx.x == 0) {
     // both increments are in flight together: one round trip at the end of a tile, not two
-    const uint32_t old = __hip_atomic_fetch_add(&t.counter[c], 1u, __ATOMIC_RELAXED,
+    const uint32_t old = __hip_atomic_fetch_add(&t.counter[c], (uint32_t)n, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
     const uint32_t d = __hip_atomic_fetch_add(t.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // threshold = tracked regions of the chunk x updates expected per element (Sec. 4.2.1)
-    const uint32_t threshold = (uint32_t)p.tpc * (uint32_t)(c == p.rank ? p.upd_first : p.upd_rest);
-    if (old + 1u == threshold) {         // the landing that reaches the threshold triggers
+    const uint32_t threshold = (uint32_t)p.tpc_t * (uint32_t)(c == p.rank ? p.upd_first : p.upd_rest);
+    if (old + (uint32_t)n == threshold) {         // the landing that reaches the threshold triggers
       if (c != p.own) {
         const uint32_t pos = __hip_atomic_fetch_add(t.queue_len, 1u, __ATOMIC_RELAXED,
                                                     __HIP_MEMORY_SCOPE_AGENT);
@@ -308,7 +318,7 @@ __device__ inline void track_count(const Plan &p, const Trk &t, int c) {
 // chunk was dispatched before this workgroup (lower block index), so the wait ends; should it
 // not (a broken launch), the workgroup gives up after kSpinLimit polls and raises the error word.
 __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_t *sh) {
-  if ((int64_t)(slot + 1) * p.tpc > p.limit || (int64_t)slot * p.tpc < p.begin)
+  if ((int64_t)(slot + 1) * p.tpc_t > p.limit || (int64_t)slot * p.tpc_t < p.begin)
     return;                                              // this chunk will not complete
   const Trk t = trk_open(p);
   int c = p.rank + slot;
@@ -369,6 +379,38 @@ __device__ inline void sched_kstep() {
   }
 }
 
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), so that the
+// index can be used where a constant is required (instruction offsets, which register).
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for_impl(F &f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for_impl<I + 1, N>(f);
+  }
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F f) {
+  static_for_impl<0, N>(f);
+}
+
+// The memory instructions of the hand-ordered main loop, one volatile statement each: they are
+// emitted in exactly the order written, and the waits they need are written out as well.  The
+// products stay compiler builtins (the compiler must know them to keep the distances the
+// hardware requires around them) and are fenced into place with scheduling barriers.
+template <int OFF>
+__device__ __forceinline__ void asm_ds_read_b128(bf16x8 &dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+// "The 8 + 8 operands of a k-step have landed": the wait carries them as in/out operands, so
+// that no product that uses them can be moved above it.
+__device__ __forceinline__ void asm_wait_operands(bf16x8 (&a)[8], bf16x8 (&b)[8]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
+                 "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+               :
+               : "memory");
+}
+
 constexpr int kRingSlots = 4;         // 1-KiB LDS slots per wavefront for transposing pairs: two pairs
 
 // WAVES_M x WAVES_N wavefronts per workgroup, each producing a (BM/WAVES_M) x (BN/WAVES_N)
@@ -386,7 +428,8 @@ constexpr int kRingSlots = 4;         // 1-KiB LDS slots per wavefront for trans
 // position (piece ^ sw(k)), sw(k) = (k & 3) | ((k >> 3) & 1) << 2, which spreads the 8 k-rows
 // that 32 lanes read together over all banks.  K must be a multiple of 64 in this layout.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE, int BKN>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
+__attribute__((amdgpu_waves_per_eu((BM / WAVES_M) * (BN / WAVES_N) > 8192 ? 1 : 2)))
 void gemm_tile_kernel(const Plan p) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wavefront tile
@@ -407,7 +450,14 @@ void gemm_tile_kernel(const Plan p) {
   static_assert((FN & (FN - 1)) == 0, "block index -> (row block, column block) by shifts");
   static_assert(NSTAGE * kStageBytes <= 160 * 1024, "LDS");
 
-  __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes];
+  // Four wavefronts of 128 x 128 (one per SIMD) run the hand-ordered main loop and add the
+  // incoming partial on the way out; B stored N x K only.
+  constexpr bool kAsmLoop = (NW == 4 && FM == 8 && FN == 8 && NSTAGE == 2 && !BKN);
+  // Their pair transpositions get LDS of their own (4 KiB per wavefront) behind the stages.
+  constexpr int kScrOff = kAsmLoop ? NSTAGE * kStageBytes : 0;
+  static_assert(kScrOff + NW * kRingSlots * 1024 <= 160 * 1024, "LDS");
+
+  __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * kStageBytes + (kAsmLoop ? NW * kRingSlots * 1024 : 0)];
 
   // Persistent workgroups: workgroup w takes grid positions w, w + gridDim.x, ... in order (a
   // position is a tile or a piece of release work).  The tracking of a finished tile is
@@ -423,11 +473,16 @@ void gemm_tile_kernel(const Plan p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   int pending_c = -1;                          // chunk of a tile whose stores are issued but not counted
+  int pending_n = 1;                           //   and the tracked tiles it covers
   auto flush_pending = [&]() {
-    if (MODE == kModeFused && pending_c >= 0) track_tile(p, trk, pending_c);
+    if (MODE == kModeFused && pending_c >= 0) track_tile(p, trk, pending_c, pending_n);
     pending_c = -1;
   };
 
+  // The accumulators live across tiles: the hand-ordered kernel fills them with the NEXT tile's
+  // incoming partial while the current tile's sums are on their way out (`have_in`).
+  f32x4 acc[BM / WAVES_M / 16][BN / WAVES_N / 16];
+  bool have_in = false;
   for (int pos = blockIdx.x; pos < p.total_blocks * p.split_k; pos += gridDim.x) {
   // split-K (two-writer mode only): `split_k` consecutive positions share a tile, part j taking
   // K-slabs [j q, (j+1) q) of the K / 64 full ones, the last part also what is left over
@@ -456,6 +511,16 @@ void gemm_tile_kernel(const Plan p) {
   const int col_hi = col_lo + p.W;
   const int n0 = col_lo + tl.nj * BN;
 
+  const int nkf = Kpart / kBK;                   // full slabs
+  const int ktail = Kpart - nkf * kBK;           // leftover elements of K (a multiple of 8)
+  // Workgroups that run on different XCDs walk K from different starting slabs (and wrap
+  // around): at any moment the chip then reads 8 different K ranges of A and B instead of one,
+  // which spreads the traffic over the memory channels, and what one XCD misses in its L2
+  // another has usually brought into the memory-side cache already.  Workgroups of one XCD
+  // (same index modulo the group count) keep the same offset, so they still share slabs in L2.
+  const int koff = p.k_groups > 1
+                       ? (int)(((uint32_t)(blockIdx.x % (uint32_t)p.k_groups) * (uint32_t)nkf) / (uint32_t)p.k_groups)
+                       : 0;
   // ---- global -> LDS copy addressing.  Copy q of this wavefront fills 8 LDS rows (1 KiB):
   // lane l lands in row l / 8, position l % 8, so it must fetch chunk (l % 8) ^ swz(row).
   const int cp_row = lane / kCPR;
@@ -501,6 +566,8 @@ void gemm_tile_kernel(const Plan p) {
 #pragma clang diagnostic ignored "-Winline-asm"
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
   auto issue_copies = [&](int kt, int stage, int q0, int q1) {
+    kt += koff;                                   // slab kt of this workgroup's walk over K
+    if (kt >= nkf) kt -= nkf;
     const char *a = Ap + (int64_t)kt * (kBK * 2);
     const char *b = Bp + (BKN ? (int64_t)kt * kBK * p.ldb * 2 : (int64_t)kt * (kBK * 2));
     const uint32_t dst = lds_base + stage * kStageBytes;
@@ -538,12 +605,10 @@ void gemm_tile_kernel(const Plan p) {
   const int trB = kBOff + (8 * fq + (fr >> 2)) * kBRowBytes + (fr & 3) * 8;
   const int trSw = ((fr >> 2) | ((fq & 1) << 2)) & kSwMask;
 
-  const int nkf = Kpart / kBK;                   // full slabs
-  const int ktail = Kpart - nkf * kBK;           // leftover elements of K (a multiple of 8)
-
   // NSTAGE-1 slabs are always in flight.  Past the last slab the copies are repeated into
   // stages nobody reads any more, so every wait below is for the same number of younger copies.
   if (nkf > 0) issue_slab(0, 0);
+  if (kAsmLoop && nkf > 0) issue_slab(min(1, nkf - 1), 1);   // (its scratch is not in the stages)
 
   // ---- accumulators start from the incoming partial (fused) or zero.
   // Block (i, j), element e of this lane: row 16*i + (lane & 15), column 16*j + 4*(lane >> 4) + e
@@ -586,31 +651,38 @@ void gemm_tile_kernel(const Plan p) {
   static_assert(FN % 2 == 0, "pairs");
   // Every access to R, C or a forward slot is (uniform base) + (32-bit byte offset of the lane),
   // the offset formed per block when it is needed: byte sizes of these arrays stay below 4 GiB.
-  f32x4 acc[FM][FN];
+  if (!have_in) {
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (MODE == kModeFused && !store_only && !two_writers) {
-    // The incoming partial, loaded before the main loop: every pair as two full-line accesses
-    // (8 rows x 128 bytes), all in flight together, landing in the pair's accumulator registers;
-    // then pair by pair through LDS into the accumulator layout.  The scratch is the last
-    // stage, which no copy touches before the main loop's first barrier.
+      for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // The incoming partial: every pair as two full-line accesses (8 rows x 128 bytes), all in
+  // flight together, landing in the pair's accumulator registers; then pair by pair through LDS
+  // into the accumulator layout, so that the products accumulate on top of it.  (The scratch is
+  // the last stage, which no copy touches before the main loop's first barrier; the hand-ordered
+  // kernel has scratch of its own.)
+  auto in_pairs_load = [&](int m_lo, int n_lo, int col_end, bool whole) {
     const uint32_t ld_in = (uint32_t)p.ldr;
     const __amdgpu_buffer_rsrc_t in_rsrc = make_rsrc(p.R, (uint32_t)p.M * ld_in * 4u);
     uint32_t in_l[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
-      in_l[h] = ((uint32_t)(rw0 + u_row[h]) * ld_in + (uint32_t)(cw0 + u_col[h])) * 4u;
+      in_l[h] = ((uint32_t)(m_lo + u_row[h]) * ld_in + (uint32_t)(n_lo + u_col[h])) * 4u;
 #pragma unroll
     for (int t = 0; t < NPAIR; ++t) {
       const int i = t / UJ, jj = t % UJ;
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
-        if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
-          acc[i][2 * jj + h] = load_stream(in_rsrc, in_l[h], ((uint32_t)(16 * i) * ld_in + (uint32_t)(32 * jj)) * 4u);
+      for (int h = 0; h < 2; ++h) {
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (whole || (m_lo + 16 * i + u_row[h] < p.M && n_lo + 32 * jj + u_col[h] < col_end))
+          v = load_stream(in_rsrc, in_l[h], ((uint32_t)(16 * i) * ld_in + (uint32_t)(32 * jj)) * 4u);
+        acc[i][2 * jj + h] = v;
+      }
     }
-    char *scr = lds + (NSTAGE - 1) * kStageBytes + wave * (kRingSlots * 1024);
+  };
+  auto in_pairs_transpose = [&]() {
+    char *scr = lds + (kAsmLoop ? kScrOff : (NSTAGE - 1) * kStageBytes) + wave * (kRingSlots * 1024);
 #pragma unroll
     for (int t = 0; t < NPAIR; ++t) {
       const int i = t / UJ, jj = t % UJ;
@@ -621,13 +693,103 @@ void gemm_tile_kernel(const Plan p) {
       acc[i][2 * jj + 1] = *(const f32x4 *)(slot + u_acc[1]);
       if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  // A persistent workgroup of the hand-ordered kernel requests the NEXT tile's incoming partial
+  // at the end of a tile's epilogue, right behind that tile's stores (`have_in`): the loads are
+  // then on their way while the workgroup decodes its next position and requests its first slabs.
+  if (MODE == kModeFused && !store_only && !two_writers) {
+    if (!have_in) in_pairs_load(rw0, cw0, col_hi, full);
+    in_pairs_transpose();
   }
+  have_in = false;
 
+  if constexpr (kAsmLoop) {
+  // ---- main loop, hand-ordered.  One wavefront per SIMD: nobody else fills the matrix pipe while
+  // this one waits, so no wait may be exposed.  Two LDS stages, two sets of operand registers.  A
+  // k-step is 64 products; the 16 operand reads of the next k-step go out one per three
+  // products, early enough to have landed when the k-step ends, and the 16 copies of the slab
+  // after next one per three products of a slab's second k-step.  One barrier per slab:
+  //   second k-step of slab t  | reads: first k-step of slab t+1  | copies: slab t+2 -> stage of t
+  //   first k-step of slab t+1 | reads: second k-step of slab t+1
+  //   wait for own reads and copies, barrier   (slab t+2 visible; all are done reading slab t+1)
+  if (nkf > 0) {
+    bf16x8 xa[2][FM], xb[2][FN];
+    uint32_t adA[KS], adB[KS];                   // this lane's operand rows of k-step kk, stage 0
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      adA[kk] = lds_base + fragA[kk];
+      adB[kk] = lds_base + fragB[kk];
+    }
+    // read r of a k-step's FM + FN, in the order the products need them: B block 0, A block 0,
+    // the other B blocks, the other A blocks
+    auto read_op = [&](auto R, auto SET, uint32_t a_addr, uint32_t b_addr) {
+      constexpr int r = decltype(R)::value, set = decltype(SET)::value;
+      if constexpr (r == 0) asm_ds_read_b128<0>(xb[set][0], b_addr);
+      else if constexpr (r == 1) asm_ds_read_b128<0>(xa[set][0], a_addr);
+      else if constexpr (r <= FN) asm_ds_read_b128<(r - 1) * 16 * kRowBytes>(xb[set][r - 1], b_addr);
+      else asm_ds_read_b128<(r - FN) * 16 * kRowBytes>(xa[set][r - FN], a_addr);
+    };
+    // One k-step: the products of operand set CS.  READS: the next k-step's operands go into the
+    // other set from (a_addr, b_addr).  COPIES: slab kt_c goes into stage st_c.
+    auto kstep = [&](auto CS, auto READS, auto COPIES, uint32_t a_addr, uint32_t b_addr, int kt_c, int st_c) {
+      constexpr int cs = decltype(CS)::value;
+      asm_wait_operands(xa[cs], xb[cs]);                      // this k-step's operands have landed
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<FM * FN>([&](auto Mi) {
+        constexpr int m = decltype(Mi)::value, i = m / FN, j = m % FN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xb[cs][j], xa[cs][i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);                    // nothing moves across: the order is as written
+        if constexpr (decltype(READS)::value && m % 3 == 0 && m / 3 < FM + FN) {
+          read_op(std::integral_constant<int, m / 3>{}, std::integral_constant<int, cs ^ 1>{}, a_addr, b_addr);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (decltype(COPIES)::value && m % 3 == 1 && m / 3 < NL) {
+          issue_copies(kt_c, st_c, m / 3, m / 3 + 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      });
+    };
+    using std::false_type;
+    using std::true_type;
+    constexpr std::integral_constant<int, 0> set0{};
+    constexpr std::integral_constant<int, 1> set1{};
+
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NL) : "memory");   // slab 0 landed (slab 1 may be on its way)
+    __builtin_amdgcn_s_barrier();
+    static_for<FM + FN>([&](auto R) { read_op(R, set0, adA[0], adB[0]); });
+    kstep(set0, true_type{}, false_type{}, adA[1], adB[1], 0, 0);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();                  // slab 1 visible
+    if (MODE == kModeFused && pending_c >= 0) {    // the previous tile's stores are acknowledged too:
+      track_count(p, trk, pending_c, pending_n);   //   every wavefront has just waited for vmcnt(0)
+      pending_c = -1;
+    }
+    uint32_t so = 0;                               // byte offset of the stage that holds slab kt
+    for (int kt = 0; kt < nkf - 2; ++kt) {
+      const uint32_t sn = so ^ (uint32_t)kStageBytes;
+      kstep(set1, true_type{}, true_type{}, adA[0] + sn, adB[0] + sn, kt + 2, (int)(so / kStageBytes));
+      kstep(set0, true_type{}, false_type{}, adA[1] + sn, adB[1] + sn, 0, 0);
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      so = sn;
+    }
+    if (nkf > 1) {                                 // slab nkf-2's second k-step, slab nkf-1's first
+      const uint32_t sn = so ^ (uint32_t)kStageBytes;
+      kstep(set1, true_type{}, false_type{}, adA[0] + sn, adB[0] + sn, 0, 0);
+      kstep(set0, true_type{}, false_type{}, adA[1] + sn, adB[1] + sn, 0, 0);
+    }
+    kstep(set1, false_type{}, false_type{}, 0u, 0u, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  }
+  if constexpr (!kAsmLoop) {
   if (nkf > 0) {
 #pragma unroll
     for (int st = 1; st < NSTAGE - 1; ++st) issue_slab(min(st, nkf - 1), st);
   }
 
+  }
   // Two sets of operand registers.  Micro-step u = (k-step kk, row pass h) reads FMH row blocks
   // of A (set u & 1) and, on the first pass of a k-step, the FN column blocks of B (set kk & 1),
   // while the products of micro-step u-1 are issued.
@@ -665,6 +827,7 @@ void gemm_tile_kernel(const Plan p) {
                                                                       acc[h * FMH + i][j], 0, 0, 0);
   };
 
+  if constexpr (!kAsmLoop) {
   // ---- main loop: slab kt is multiplied while the next NSTAGE-1 slabs are in flight.  The
   // products of a slab's last micro-step are issued after the next barrier, under the next
   // slab's first LDS reads.  An iteration is: wait + barrier; k-step 0, with the next slab's
@@ -674,7 +837,7 @@ void gemm_tile_kernel(const Plan p) {
     __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the incoming partial) landed
     __builtin_amdgcn_s_barrier();
     if (MODE == kModeFused && pending_c >= 0) {    // (also older: the previous tile's stores)
-      track_count(p, trk, pending_c);
+      track_count(p, trk, pending_c, pending_n);
       pending_c = -1;
     }
     issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
@@ -709,6 +872,7 @@ void gemm_tile_kernel(const Plan p) {
     }
     mfma_u(US - 1);
     __builtin_amdgcn_s_waitcnt(kWaitVm0);          // drain the repeated copies
+  }
   }
   asm volatile("" ::: "memory");
 
@@ -754,7 +918,55 @@ void gemm_tile_kernel(const Plan p) {
     out_base = p.R;
     col_org = 0;
   }
-  if (to_fwd && (p.flags & kFlagFwdBf16)) {
+  if constexpr (kAsmLoop) {
+    // Pair by pair through this wavefront's own 4 KiB of LDS: written in the accumulator layout,
+    // read back linearly, stored 8 rows x 128 bytes per instruction.  (Two-writer mode and
+    // bfloat16 forward slots written directly are served by the eight-wavefront kernel.)
+    const __amdgpu_buffer_rsrc_t out_rsrc = make_rsrc(out_base, (uint32_t)p.M * ld_out * 4u);
+    char *scr = lds + kScrOff + wave * (kRingSlots * 1024);
+    uint32_t out_u[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      out_u[h] = ((uint32_t)(rw0 + u_row[h]) * ld_out + (uint32_t)(cw0 - col_org + u_col[h])) * 4u;
+    // the next grid position of this workgroup: if it is a tile that takes an incoming partial,
+    // its accumulator blocks are requested once this tile's sums have been stored
+    bool next_in = false, next_full = false;
+    int next_rw0 = 0, next_cw0 = 0, next_col_hi = 0;
+    if (MODE == kModeFused && p.split_k == 1 && pos + (int)gridDim.x < p.total_blocks) {
+      Tile tn;
+      int slot_n = 0, agent_n = 0;
+      if (decode_block(p, pos + (int)gridDim.x, tn, slot_n, agent_n) == kRoleTile &&
+          !((p.flags & kFlagStep0StoreOnly) && tn.s == 0)) {
+        next_in = true;
+        next_col_hi = tn.c * p.W + p.W;
+        next_rw0 = tn.mi * BM + wm * WM;
+        next_cw0 = tn.c * p.W + tn.nj * BN + wn * WN;
+        next_full = (next_rw0 + WM <= p.M) && (next_cw0 + WN <= next_col_hi);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < NPAIR; ++t) {
+      const int i = t / UJ, jj = t % UJ;
+      char *slot = scr + ((2 * t) & (kRingSlots - 1)) * 1024;
+      *(f32x4 *)(slot + u_acc[0]) = acc[i][2 * jj];
+      *(f32x4 *)(slot + u_acc[1]) = acc[i][2 * jj + 1];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane * 16);
+        if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
+          store_agent(out_rsrc, out_u[h], ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u, v);
+      }
+      // keep the scheduler from running many pairs ahead: it would park their values in registers
+      if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+    // (after the last store, not between the stores: reads and writes that alternate cost the
+    // memory more than a burst of each)
+    if (next_in) {
+      __builtin_amdgcn_sched_barrier(0);
+      in_pairs_load(next_rw0, next_cw0, next_col_hi, next_full);
+    }
+    have_in = next_in;
+  } else if (to_fwd && (p.flags & kFlagFwdBf16)) {
     // Forward slot in bfloat16: a row of the wavefront tile (64 columns) is one 128-byte line.
     // Row of blocks by row of blocks through LDS: the lane's four rounded sums of each block
     // (8 bytes) go to row (lane & 15), columns 16 j + 4 (lane >> 4) of a 16-row x 128-byte
@@ -849,6 +1061,7 @@ void gemm_tile_kernel(const Plan p) {
   if (MODE == kModeFused) {
     if (nkf == 0) flush_pending();               // (no main loop ran: nothing was counted on the way)
     pending_c = tl.c;
+    pending_n = min(p.pair_m, p.Mt_t - tl.mi * p.pair_m);
   }
   }  // grid positions
   flush_pending();

@@ -146,3 +146,28 @@ def test_three_tiles_per_workgroup_float_every_element(gpu, oracle, tile):
         assert d.max() <= 1e-4 * scale
         assert gpu.rel_err(got[name], want[name]) <= 1e-5
     _check_ints(got, want, want["own"])
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("direct", [True, False])
+@pytest.mark.parametrize("rng_kind", ["all", "step1", "steps12", "cut"])
+def test_tracked_tiles_of_128_rows_computed_in_pairs(gpu, oracle, rng_kind, direct, unfused):
+    """128 x 256 tracked tiles: over ranges of whole ring steps the tile kernel computes two of
+    them as one 256 x 256 workgroup tile and counts both (the last tile row, here the 19th of a
+    column, stands alone); a range that cuts a step falls back to one workgroup per tracked
+    tile.  Counters, flags, queue and every element must not care."""
+    M, N, K, tp, rank, tile = 2330, 3 * 1304, 200, 3, 1, (128, 256)
+    tpc = oracle.tiles_per_chunk(M, N, tp, *tile)
+    assert tpc == 19 * 6
+    begin, limit = {"all": (0, -1), "step1": (tpc, 2 * tpc), "steps12": (tpc, 3 * tpc),
+                    "cut": (tpc + 1, 2 * tpc + 7)}[rng_kind]
+    print(f"range=[{begin},{limit}) of {tp * tpc} direct={direct} unfused={unfused}", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1234)
+    sent = np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, tile_begin=begin, tile_limit=limit,
+                             fwd_direct=direct, fwd_init=sent)
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT if direct else 0,
+                      tile_begin=begin, tile_limit=limit, unfused=unfused, ldr_pad=8)
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    _check_ints(got, want, want["own"])
