@@ -282,3 +282,28 @@ def release_ready(R, fwd, ready, P, r, fwd_bf16=False):
             chunk = R[:, c * W:(c + 1) * W]
             fwd[s] = to_bf16_bits(chunk) if fwd_bf16 else chunk
     return fwd
+
+
+def all_gather_chunk(P, r, g):
+    """Chunk that rank r receives at step g = 0 .. P-2 of the ring all-gather that follows the
+    reduce-scatter (Sec. 2.3: like the reduce-scatter but without reductions, N-1 steps until
+    every device has all the reduced chunks; same ring, Sec. 4.1: rank r receives from rank
+    r+1).  At step 0 rank r+1 passes on the chunk it owns, ((r+1) - 1) mod P = r; at step g it
+    passes on what it received at step g-1, so rank r receives chunk (r + g) mod P."""
+    if not (0 <= r < P and 0 <= g < P - 1):
+        raise ValueError("all-gather: rank or step out of range")
+    return (r + g) % P
+
+
+def all_gather_step(R_upstream, R, P, r, g):
+    """One step of the ring all-gather on rank r: the chunk all_gather_chunk(P, r, g) is copied,
+    unchanged, from the upstream neighbour's buffer into the same columns of this rank's.
+    Returns the new R (M, N) fp32."""
+    R_upstream = np.asarray(R_upstream, dtype=np.float32)
+    out = np.array(R, dtype=np.float32, copy=True)
+    if R_upstream.shape != out.shape or out.shape[1] % P:
+        raise ValueError("all-gather: shapes")
+    W = out.shape[1] // P
+    c = all_gather_chunk(P, r, g)
+    out[:, c * W:(c + 1) * W] = R_upstream[:, c * W:(c + 1) * W]
+    return out

@@ -212,6 +212,40 @@ def test_emulated_ring_closes_on_unsliced_gemm(oracle, P):
         assert np.array_equal(out[r]["owned"], whole[:, own * W:(own + 1) * W].astype(np.float32))
 
 
+@pytest.mark.parametrize("P", [2, 4, 5])
+def test_all_gather_after_the_ring_gives_every_rank_the_unsliced_gemm(oracle, P):
+    """Sec. 2.3: reduce-scatter, then an all-gather of N-1 steps without reductions, is an
+    all-reduce: every rank ends up with the whole sum.  The sums are those of the emulated ring
+    above; the all-gather schedule is pinned by (a) the chunk a rank receives first being the one
+    its upstream neighbour owns, (b) each later one being what that neighbour received a step
+    earlier, (c) a rank receiving every chunk but its own exactly once, and (d) the result."""
+    M, W, ks = 8, 6, 16
+    N, Kfull = P * W, P * ks
+    a, b, _ = wl.make_integer_inputs(M, N, Kfull, seed=77 + P)
+    whole = (wl.bf16_bits_to_f32(a).astype(np.int64) @ wl.bf16_bits_to_f32(b).astype(np.int64).T
+             ).astype(np.float32)
+    for r in range(P):
+        own = oracle.chunk_order(P, r)[1]
+        up_own = oracle.chunk_order(P, (r + 1) % P)[1]
+        got = [oracle.all_gather_chunk(P, r, g) for g in range(P - 1)]
+        assert got[0] == up_own                                                  # (a)
+        assert all(got[g] == oracle.all_gather_chunk(P, (r + 1) % P, g - 1) for g in range(1, P - 1))  # (b)
+        assert sorted(got + [own]) == list(range(P))                             # (c)
+    with pytest.raises(ValueError):
+        oracle.all_gather_chunk(P, 0, P - 1)
+    # rank r's buffer after the reduce-scatter: its own chunk reduced, garbage elsewhere
+    R = []
+    for r in range(P):
+        own = oracle.chunk_order(P, r)[1]
+        buf = np.full((M, N), -1000.0 - r, dtype=np.float32)
+        buf[:, own * W:(own + 1) * W] = whole[:, own * W:(own + 1) * W]
+        R.append(buf)
+    for g in range(P - 1):
+        R = [oracle.all_gather_step(R[(r + 1) % P], R[r], P, r, g) for r in range(P)]   # all ranks at once
+    for r in range(P):
+        assert np.array_equal(R[r], whole)                                       # (d)
+
+
 @pytest.mark.parametrize("P", [3, 4])
 def test_ring_steps_as_tile_ranges_compose_to_the_whole_path(oracle, P):
     """One ring step is the range [s*tpc, (s+1)*tpc) of the issue order (Sec. 4.1).  Running the
