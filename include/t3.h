@@ -272,6 +272,24 @@ t3_status t3_upstream_update(const t3_problem *p, const float *incoming, float *
 t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
                             const uint32_t *track, void *stream);
 
+/*
+ * One step of the ring all-gather that follows the reduce-scatter (Sec. 2.3: N-1 steps without
+ * reductions until every device has all the reduced chunks; the "Sequential" all-gather of
+ * Sec. 5.3).  Same ring as the reduce-scatter (Sec. 4.1): at step g = 0 .. tp-2 rank `rank`
+ * takes chunk (rank + g) mod tp -- at step 0 the chunk its upstream neighbour rank+1 owns, later
+ * what that neighbour took a step earlier -- unchanged, from the neighbour's buffer into the
+ * same columns of its own.  After tp-1 steps R holds all tp reduced chunks.
+ *
+ *   upstream_R  fp32 [M][ld_up]  read: the upstream neighbour's buffer (on several GPUs: the
+ *                                peer's memory; here the caller's stand-in), ld_up >= N
+ *   R           fp32 [M][ldr]    columns [c W, (c+1) W) are overwritten, the rest is untouched
+ *
+ * T3_ERR_BAD_SHAPE if step is outside [0, tp-1); leading dimensions and W multiples of 4,
+ * pointers 16-byte aligned (T3_ERR_ALIGN).  Tile shape, flags and tracker play no part.
+ */
+t3_status t3_ag_step(const t3_problem *p, int32_t step, const float *upstream_R, int64_t ld_up,
+                     float *R, void *stream);
+
 const char *t3_status_string(t3_status s);
 
 /* hipError_t of the last T3_ERR_HIP on the calling thread (0 if none). */

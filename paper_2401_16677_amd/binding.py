@@ -22,7 +22,7 @@ T3_STATIC_MAX_TP = 64
 
 EXPORTS = ["t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
            "t3_track_words", "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
-           "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static",
+           "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static", "t3_ag_step",
            "t3_status_string", "t3_last_hip_error"]
 
 
@@ -70,6 +70,7 @@ def lib():
         L.t3_track_reset.argtypes = [i32, vp, vp]
         L.t3_gemm_rs_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp]
         L.t3_gemm_rs_fused_static.argtypes = [pp, vp, vp, vp, vp, vp, vp]
+        L.t3_ag_step.argtypes = [pp, i32, vp, i64, vp, vp]
         L.t3_gemm.argtypes = [pp, vp, vp, vp, vp]
         L.t3_rs_reduce.argtypes = [pp, vp, vp, vp, vp, vp]
         L.t3_upstream_update.argtypes = [pp, vp, vp, vp, vp]
@@ -79,7 +80,8 @@ def lib():
         L.t3_last_hip_error.restype = i32
         for f in ("t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
                   "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
-                  "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static"):
+                  "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static",
+                  "t3_ag_step"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -176,6 +178,11 @@ def t3_gemm_rs_fused_static(p, A, B, R, fwd, track_copy=None, stream=None):
     _check(lib().t3_gemm_rs_fused_static(ctypes.byref(p), _dptr(A), _dptr(B), _dptr(R), _dptr(fwd),
                                          _dptr(track_copy), _stream(stream)),
            "t3_gemm_rs_fused_static")
+
+
+def t3_ag_step(p, step, upstream_R, R, ld_up=None, stream=None):
+    _check(lib().t3_ag_step(ctypes.byref(p), step, _dptr(upstream_R), p.ldr if ld_up is None else ld_up,
+                            _dptr(R), _stream(stream)), "t3_ag_step")
 
 
 def t3_gemm(p, A, B, C, stream=None):

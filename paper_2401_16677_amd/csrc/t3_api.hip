@@ -629,4 +629,21 @@ t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
                 dim3(t3k::kThreads), static_cast<hipStream_t>(stream), q);
 }
 
+t3_status t3_ag_step(const t3_problem *p, int32_t step, const float *upstream_R, int64_t ld_up,
+                     float *R, void *stream) {
+  const t3_status st = check_shape(p);
+  if (st != T3_OK) return st;
+  if (step < 0 || step >= p->tp - 1) return T3_ERR_BAD_SHAPE;
+  if (!upstream_R || !R) return T3_ERR_NULL;
+  const int64_t W = p->N / p->tp;
+  if (p->ldr < p->N || ld_up < p->N) return T3_ERR_BAD_SHAPE;
+  if (p->ldr % 4 || ld_up % 4 || W % 4 || !aligned16(R) || !aligned16(upstream_R)) return T3_ERR_ALIGN;
+  if (p->M == 0 || W == 0) return T3_OK;
+  const int64_t c = (p->rank + step) % p->tp;    // what the upstream neighbour owned, or got a step ago
+  const unsigned rows_per_block = t3k::kThreads / 64;
+  const unsigned blocks = (unsigned)(ceil_div(p->M, rows_per_block) < 4096 ? ceil_div(p->M, rows_per_block) : 4096);
+  return launch(t3k::ag_copy_kernel, dim3(blocks), dim3(t3k::kThreads), static_cast<hipStream_t>(stream),
+                upstream_R + c * W, ld_up, R + c * W, (int64_t)p->ldr, (int32_t)p->M, (int32_t)W);
+}
+
 }  // extern "C"

@@ -1194,6 +1194,29 @@ __global__ void track_reset_kernel(uint32_t *track, int P) {
   }
 }
 
+// One step of the ring all-gather (Sec. 2.3): a chunk of M rows x W columns moves, unchanged,
+// from the upstream neighbour's buffer into the same columns of this rank's.  One wavefront per
+// row and pass, 16 bytes per lane, four accesses in flight per lane.
+__global__ __launch_bounds__(kThreads) void ag_copy_kernel(const float *src, int64_t ld_src, float *dst,
+                                                           int64_t ld_dst, int32_t M, int32_t W) {
+  const int lane = threadIdx.x & 63;
+  const int W4 = W >> 2;
+  const int waves = (int)(gridDim.x * (blockDim.x >> 6));
+  for (int r = (int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)); r < M; r += waves) {
+    const f32x4 *s4 = (const f32x4 *)(src + (int64_t)r * ld_src);
+    f32x4 *d4 = (f32x4 *)(dst + (int64_t)r * ld_dst);
+    for (int c0 = lane; c0 < W4; c0 += 4 * 64) {
+      f32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * 64 < W4) v[u] = __builtin_nontemporal_load(s4 + c0 + u * 64);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * 64 < W4) __builtin_nontemporal_store(v[u], d4 + c0 + u * 64);
+    }
+  }
+}
+
 // Copies n words of tracker state (for callers that want to read the state another array holds).
 __global__ void track_copy_kernel(const uint32_t *src, uint32_t *dst, int n) {
   for (int i = threadIdx.x; i < n; i += blockDim.x)

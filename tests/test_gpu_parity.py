@@ -218,6 +218,49 @@ def test_ring_of_virtual_ranks_closes_on_unsliced_gemm(gpu, oracle, kind):
             e = gpu.rel_err(got, want)
             print(f"rank {q} owns chunk {own}: normwise error {e:.2e}", flush=True)
             assert e <= EXPECT
+    # The sequential all-gather that follows (Sec. 2.3, Sec. 5.3): P-1 steps of t3_ag_step, every
+    # rank pulling from its upstream neighbour's buffer; all ranks move together, so a step reads
+    # what the neighbour held BEFORE the step (snapshots stand in for the simultaneous transfers).
+    owned = [R_r[q][:, ((q - 1) % P) * W:(((q - 1) % P) + 1) * W].clone() for q in range(P)]
+    for g in range(P - 1):
+        snap = [r.clone() for r in R_r]
+        for q in range(P):
+            t3.t3_ag_step(t3.problem(M, N, ks, P, q), g, snap[(q + 1) % P], R_r[q])
+        torch.cuda.synchronize()
+    full = np.concatenate([owned[(c + 1) % P].cpu().numpy() for c in range(P)], axis=1)   # chunk c is rank c+1's
+    for q in range(P):
+        got = R_r[q].cpu().numpy()
+        assert np.array_equal(got, full)              # copies: bit for bit what the owners reduced
+        if kind == "integer":
+            assert np.array_equal(got, whole.astype(np.float32))
+        else:
+            assert gpu.rel_err(got, whole) <= EXPECT
+
+
+def test_all_gather_step_shapes_and_refusals(gpu, oracle):
+    """t3_ag_step on a ragged shape with padded leading dimensions: only the chunk's columns
+    change, bit for bit the oracle's step; bad steps and misaligned widths are refused."""
+    import torch
+    M, N, P, r = 301, 5 * 52, 5, 3
+    rng = np.random.default_rng(9)
+    up = rng.standard_normal((M, N + 8)).astype(np.float32)
+    mine = rng.standard_normal((M, N + 4)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    for g in range(P - 1):
+        U, R = torch.from_numpy(up).to(dev), torch.from_numpy(mine).to(dev)
+        p = t3.problem(M, N, 64, P, r, ldr=N + 4)
+        t3.t3_ag_step(p, g, U, R, ld_up=N + 8)
+        torch.cuda.synchronize()
+        want = oracle.all_gather_step(up[:, :N], mine[:, :N], P, r, g)
+        got = R.cpu().numpy()
+        assert np.array_equal(got[:, :N], want) and np.array_equal(got[:, N:], mine[:, N:])
+    for bad in (-1, P - 1):
+        with pytest.raises(t3.T3Error) as e:
+            t3.t3_ag_step(t3.problem(M, N, 64, P, r, ldr=N + 4), bad, U, R, ld_up=N + 8)
+        assert e.value.status == t3.T3_ERR_BAD_SHAPE
+    with pytest.raises(t3.T3Error) as e:
+        t3.t3_ag_step(t3.problem(M, 5 * 50, 64, P, r, ldr=N + 4), 0, U, R, ld_up=N + 8)
+    assert e.value.status == t3.T3_ERR_ALIGN
 
 
 def _run_two_writers(gpu, a, b, inc, tp, rank, tile, *, order, step0=False, tile_begin=0, tile_limit=-1,
