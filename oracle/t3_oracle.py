@@ -24,6 +24,8 @@ _lib = None
 
 B_NK = 0  # B stored N x K, K contiguous
 B_KN = 1  # B stored K x N, N contiguous
+A_MK = 0  # A stored M x K, K contiguous
+A_KM = 1  # A stored K x M, M contiguous (the transposed operand of the backward-pass GEMMs, Sec. 5.2)
 
 _c_i32 = ctypes.c_int32
 _c_i64 = ctypes.c_int64
@@ -74,12 +76,17 @@ def chunk_order(P, r):
     return order[:P].copy(), int(own.value)
 
 
-def gemm_rows(A_bits, B_bits, b_layout=B_NK, rows=None):
+def gemm_rows(A_bits, B_bits, b_layout=B_NK, rows=None, a_layout=A_MK):
     """fp64 sliced GEMM (Sec. 2.4) for all rows or the listed rows.
 
-    A_bits: uint16 (M, K) bf16 bit patterns; B_bits: uint16 (N, K) for B_NK or
-    (K, N) for B_KN.  Returns float64 (nrows, N).
+    A_bits: uint16 (M, K) bf16 bit patterns for A_MK, (K, M) for A_KM (element (m, k) of the
+    operand is then A_bits[k, m]: it is put back into (M, K) order first, which changes no
+    value); B_bits: uint16 (N, K) for B_NK or (K, N) for B_KN.  Returns float64 (nrows, N).
     """
+    if a_layout == A_KM:
+        A_bits = np.asarray(A_bits, dtype=np.uint16).T
+    elif a_layout != A_MK:
+        raise ValueError("unknown a_layout")
     A_bits = np.ascontiguousarray(A_bits, dtype=np.uint16)
     B_bits = np.ascontiguousarray(B_bits, dtype=np.uint16)
     M, K = A_bits.shape
@@ -186,7 +193,7 @@ def _new_fwd(P, M, W, fwd_init, fwd_bf16):
     return np.array(fwd_init, dtype=dt, copy=True)
 
 
-def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
+def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK, a_layout=A_MK,
                tile_limit=-1, tile_begin=0, step0_store_only=False, fwd_direct=False,
                fwd_init=None, two_writers=False, R_init=None, split_k=1, fwd_bf16=False):
     """The whole path for one rank, by the definition.
@@ -211,7 +218,7 @@ def fused_path(A_bits, B_bits, incoming, P, r, tile_m, tile_n, *, b_layout=B_NK,
         raise ValueError("N must be a multiple of P")
     W = N // P
     order, own = chunk_order(P, r)
-    C = gemm_rows(A_bits, B_bits, b_layout)
+    C = gemm_rows(A_bits, B_bits, b_layout, a_layout=a_layout)
     S = reduce_rows(C, incoming, P, skip_chunk=int(order[0]) if step0_store_only else -1)
     mask, L, B0 = executed_mask(M, N, P, r, tile_m, tile_n, tile_limit, tile_begin)
     if two_writers:

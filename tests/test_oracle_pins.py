@@ -56,6 +56,32 @@ def test_gemm_row_subset_and_kn_layout(oracle):
                               oracle.gemm_rows(sq_a, np.ascontiguousarray(sq_b.T)))
 
 
+def test_gemm_a_stored_k_by_m(oracle):
+    """A stored K x M (the transposed operand of the backward-pass GEMMs, Sec. 5.2): the same
+    product as with the M x K storage of the same operand, checked against an exact integer
+    matmul written on the K x M array itself; and not the product of the transposed operand."""
+    M, N, K, P = 12, 8, 16, 2
+    a, b, inc = _small(5, M, N, K, P)
+    at = np.ascontiguousarray(a.T)                    # (K, M) storage
+    full = oracle.gemm_rows(a, b)
+    assert np.array_equal(oracle.gemm_rows(at, b, a_layout=oracle.A_KM), full)
+    ai = wl.bf16_bits_to_f32(at).astype(np.float64)   # exact small values
+    bi = wl.bf16_bits_to_f32(b).astype(np.float64)
+    brute = np.array([[sum(ai[k, m] * bi[n, k] for k in range(K)) for n in range(N)] for m in range(M)])
+    assert np.allclose(oracle.gemm_rows(at, b, a_layout=oracle.A_KM), brute, rtol=0, atol=1e-12)
+    rows = np.array([11, 0, 3], dtype=np.int32)
+    assert np.array_equal(oracle.gemm_rows(at, b, rows=rows, a_layout=oracle.A_KM), full[rows])
+    bt = np.ascontiguousarray(b.T)
+    assert np.array_equal(oracle.gemm_rows(at, bt, b_layout=oracle.B_KN, a_layout=oracle.A_KM), full)
+    sq_a, sq_b, _ = _small(6, 8, 8, 8, 2)             # square: a wrong reading would go unnoticed by shape
+    assert not np.array_equal(oracle.gemm_rows(sq_a, sq_b), oracle.gemm_rows(sq_a, sq_b, a_layout=oracle.A_KM))
+    want = oracle.fused_path(a, b, inc, P, 1, 4, 4)
+    got = oracle.fused_path(at, b, inc, P, 1, 4, 4, a_layout=oracle.A_KM)
+    assert np.array_equal(got["R"], want["R"]) and np.array_equal(got["fwd"], want["fwd"])
+    with pytest.raises(ValueError):
+        oracle.gemm_rows(a, b, a_layout=7)
+
+
 def test_gemm_integer_exact_against_int64(oracle):
     M, N, K = 33, 40, 200
     a, b, inc = wl.make_integer_inputs(M, N, K, seed=5)
