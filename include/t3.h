@@ -52,6 +52,13 @@ typedef enum {
                   (T3_ERR_UNSUPPORTED otherwise) and N/tp a multiple of 8 (T3_ERR_ALIGN)            */
 } t3_b_layout;
 
+typedef enum {
+  T3_A_MK = 0, /* A stored M x K, K contiguous: element (m,k) at A[m*lda + k]                        */
+  T3_A_KM = 1  /* A stored K x M, M contiguous: element (m,k) at A[k*lda + m] (the transposed operand
+                  of the backward-pass GEMMs, Sec. 5.2).  K must then be a multiple of 64
+                  (T3_ERR_UNSUPPORTED otherwise) and M a multiple of 8 (T3_ERR_ALIGN)               */
+} t3_a_layout;
+
 /* flags */
 #define T3_FLAG_STEP0_STORE_ONLY 1u /* the first chunk produced (order[0]) has no upstream data yet:
                                        it is stored, not added to R (Sec. 4.1, Sec. 4.4)             */
@@ -80,8 +87,8 @@ typedef struct {
   int32_t tp, rank;       /* ring size and this rank's position                                      */
   int32_t tile_m, tile_n; /* output tile = tracker granularity; 0,0 = t3_default_tile()              */
   int32_t b_layout;       /* t3_b_layout                                                             */
-  int64_t lda, ldb;       /* leading dimensions of A (>= K) and B (>= K for NK, >= N for KN), in
-                             bf16 elements, multiples of 8                                           */
+  int64_t lda, ldb;       /* leading dimensions of A (>= K for MK, >= M for KM) and B (>= K for NK,
+                             >= N for KN), in bf16 elements, multiples of 8                          */
   int64_t ldr;            /* leading dimension of R (>= N), in floats, multiple of 4                 */
   int64_t ldc;            /* leading dimension of C (>= N) for t3_gemm / t3_rs_reduce, multiple of 4 */
   int64_t tile_limit;     /* < 0: run every tile.  Otherwise only tiles whose issue index is below
@@ -101,6 +108,8 @@ typedef struct {
                              software stand-in for the arbitration policy of Sec. 4.5, which holds
                              communication accesses back while the producer is memory-bound.
                              < 0 is T3_ERR_BAD_SHAPE                                                */
+  int32_t a_layout;       /* t3_a_layout; with T3_A_KM lda >= M                                      */
+  int32_t reserved;       /* must be 0                                                               */
 } t3_problem;
 
 /*
@@ -114,7 +123,8 @@ typedef struct {
  *
  * Supported (tile_m, tile_n): (256,256), (256,128), (128,256), (128,128).
  *
- * Size limits (T3_ERR_UNSUPPORTED beyond them): M*lda and N*ldb below 2^31 elements;
+ * Size limits (T3_ERR_UNSUPPORTED beyond them): A and B below 2^31 elements each, leading
+ * dimension included (M*lda or K*lda, N*ldb or K*ldb);
  * M*ldr*4 and M*ldc*4 below 2^32 bytes (the kernels address R, C and a forward slot with
  * 32-bit byte offsets from a uniform base); fewer than 2^31 tiles.
  *
@@ -195,7 +205,7 @@ t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream);
  * that completes a chunk marks it ready and, for forwarded chunks, appends it to the
  * trigger queue, which releases the chunk into its forward slot (Sec. 4.2.2).
  *
- *   A    bf16 [M][lda]      read
+ *   A    bf16, see a_layout read
  *   B    bf16, see b_layout read
  *   R    fp32 [M][ldr]      in: incoming partials.  out: incoming + C on every executed
  *                           tile; with T3_FLAG_FWD_DIRECT only the own chunk is updated

@@ -14,6 +14,7 @@ T3_OK = 0
 T3_ERR_NULL, T3_ERR_BAD_SHAPE, T3_ERR_BAD_TILE, T3_ERR_ALIGN, T3_ERR_UNSUPPORTED, T3_ERR_HIP = \
     1, 2, 3, 4, 5, 6
 T3_B_NK, T3_B_KN = 0, 1
+T3_A_MK, T3_A_KM = 0, 1
 T3_FLAG_STEP0_STORE_ONLY = 1
 T3_FLAG_FWD_DIRECT = 2
 T3_FLAG_TWO_WRITERS = 4
@@ -35,7 +36,8 @@ class T3Problem(ctypes.Structure):
                 ("ldr", ctypes.c_int64), ("ldc", ctypes.c_int64),
                 ("tile_limit", ctypes.c_int64), ("flags", ctypes.c_uint32),
                 ("tile_begin", ctypes.c_int64), ("split_k", ctypes.c_int32),
-                ("upstream_agents", ctypes.c_int32)]
+                ("upstream_agents", ctypes.c_int32), ("a_layout", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class T3Error(RuntimeError):
@@ -98,12 +100,12 @@ def _check(status, what):
 
 def problem(M, N, K, tp, rank, tile_m=0, tile_n=0, b_layout=T3_B_NK, lda=None, ldb=None,
             ldr=None, ldc=None, tile_limit=-1, flags=0, tile_begin=0, split_k=0,
-            upstream_agents=0):
+            upstream_agents=0, a_layout=T3_A_MK):
     return T3Problem(M, N, K, tp, rank, tile_m, tile_n, b_layout,
-                     K if lda is None else lda,
+                     (K if a_layout == T3_A_MK else M) if lda is None else lda,
                      (K if b_layout == T3_B_NK else N) if ldb is None else ldb,
                      N if ldr is None else ldr, N if ldc is None else ldc, tile_limit, flags,
-                     tile_begin, split_k, upstream_agents)
+                     tile_begin, split_k, upstream_agents, a_layout, 0)
 
 
 def _dptr(t):

@@ -178,7 +178,7 @@ static_assert(T3_FLAG_STEP0_STORE_ONLY == t3k::kFlagStep0StoreOnly &&
                   T3_FLAG_FWD_DIRECT == t3k::kFlagFwdDirect &&
                   T3_FLAG_TWO_WRITERS == t3k::kFlagTwoWriters && T3_FLAG_FWD_BF16 == t3k::kFlagFwdBf16,
               "flag bits of the header and of the kernels");
-static_assert(sizeof(t3_problem) == 96, "layout documented in the header");
+static_assert(sizeof(t3_problem) == 104, "layout documented in the header");
 
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
@@ -222,15 +222,20 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   const int64_t W = p->N / p->tp;
   if (need & kNeedAB) {
     if (p->b_layout != T3_B_NK && p->b_layout != T3_B_KN) return T3_ERR_BAD_SHAPE;
-    const bool kn = p->b_layout == T3_B_KN;
-    if (p->lda < p->K || p->ldb < (kn ? p->N : p->K)) return T3_ERR_BAD_SHAPE;
+    if (p->a_layout != T3_A_MK && p->a_layout != T3_A_KM) return T3_ERR_BAD_SHAPE;
+    if (p->reserved != 0) return T3_ERR_BAD_SHAPE;
+    const bool kn = p->b_layout == T3_B_KN, km = p->a_layout == T3_A_KM;
+    if (p->lda < (km ? p->M : p->K) || p->ldb < (kn ? p->N : p->K)) return T3_ERR_BAD_SHAPE;
     if (p->K % 8 || p->lda % 8 || p->ldb % 8 || !aligned16(A) || !aligned16(B)) return T3_ERR_ALIGN;
+    // A stored K x M: 16-byte pieces run along M, and whole K-slabs of 64 only
+    if (km && p->M % 8) return T3_ERR_ALIGN;
+    if (km && p->K % 64) return T3_ERR_UNSUPPORTED;
     // B stored K x N: 16-byte pieces run along N, so chunks must be cut on multiples of 8
     // columns, and the transposed operand path takes whole K-slabs of 64 only
     if (kn && W % 8) return T3_ERR_ALIGN;
     if (kn && p->K % 64) return T3_ERR_UNSUPPORTED;
     // kernels address A and B with 32-bit element offsets
-    if ((int64_t)p->M * p->lda >= (1ll << 31) ||
+    if ((int64_t)(km ? p->K : p->M) * p->lda >= (1ll << 31) ||
         (int64_t)(kn ? p->K : p->N) * p->ldb >= (1ll << 31))
       return T3_ERR_UNSUPPORTED;
   }
@@ -403,7 +408,7 @@ t3_status launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
 
 inline unsigned grid_size(const t3k::Plan &q) { return (unsigned)q.total_blocks; }
 
-template <int MODE, int BKN>
+template <int MODE, int BKN, int AKM>
 t3_status launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStream_t s) {
   // Persistent workgroups: as many as the chip holds at once, each walking the grid positions.
   // With release work in the grid (default release mode) every position gets a workgroup of
@@ -419,24 +424,25 @@ t3_status launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStre
     // B stored N x K: four wavefronts of 128 x 128 with the hand-ordered main loop, which adds the
     // incoming partial on the way out.  It has no two-writer epilogue and does not write
     // bfloat16 forward slots itself: those, and B stored K x N, take the eight-wavefront kernel.
-    const bool eight = BKN || (MODE == t3k::kModeFused &&
+    const bool eight = BKN || AKM || (MODE == t3k::kModeFused &&
                                ((q.flags & t3k::kFlagTwoWriters) ||
                                 ((q.flags & t3k::kFlagFwdDirect) && (q.flags & t3k::kFlagFwdBf16))));
-    if constexpr (!BKN) {
+    if constexpr (!BKN && !AKM) {
       if (!eight) return launch(t3k::gemm_tile_kernel<256, 256, 2, 2, 2, MODE, 0>, grid, dim3(256), s, q);
     }
-    return launch(t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE, BKN>, grid, dim3(512), s, q);
+    return launch(t3k::gemm_tile_kernel<256, 256, 2, 4, 2, MODE, BKN, AKM>, grid, dim3(512), s, q);
   }
   if (tm == 256 && tn == 128)
-    return launch(t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, BKN>, grid, dim3(512), s, q);
+    return launch(t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, BKN, AKM>, grid, dim3(512), s, q);
   if (tm == 128 && tn == 256)
-    return launch(t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE, BKN>, grid, dim3(512), s, q);
-  return launch(t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE, BKN>, grid, dim3(256), s, q);
+    return launch(t3k::gemm_tile_kernel<128, 256, 2, 4, 3, MODE, BKN, AKM>, grid, dim3(512), s, q);
+  return launch(t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE, BKN, AKM>, grid, dim3(256), s, q);
 }
 
 template <int MODE>
-t3_status launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, bool b_kn, hipStream_t s) {
-  return b_kn ? launch_gemm_layout<MODE, 1>(q, tm, tn, s) : launch_gemm_layout<MODE, 0>(q, tm, tn, s);
+t3_status launch_gemm(const t3k::Plan &q, int32_t tm, int32_t tn, bool b_kn, bool a_km, hipStream_t s) {
+  if (a_km) return b_kn ? launch_gemm_layout<MODE, 1, 1>(q, tm, tn, s) : launch_gemm_layout<MODE, 0, 1>(q, tm, tn, s);
+  return b_kn ? launch_gemm_layout<MODE, 1, 0>(q, tm, tn, s) : launch_gemm_layout<MODE, 0, 0>(q, tm, tn, s);
 }
 
 }  // namespace
@@ -521,7 +527,7 @@ t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, fl
                                  fwd, track, &q, &tm, &tn, &empty);
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
-  return launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN,
+  return launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN, p->a_layout == T3_A_KM,
                                       static_cast<hipStream_t>(stream));
 }
 
@@ -547,7 +553,7 @@ t3_status t3_gemm_rs_fused_static(const t3_problem *p, const void *A, const void
   st = launch(t3k::track_reset_kernel, dim3(1), dim3(256), s, track, (int)p->tp);
   if (st != T3_OK) return st;
   if (!empty) {
-    st = launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN, s);
+    st = launch_gemm<t3k::kModeFused>(q, tm, tn, p->b_layout == T3_B_KN, p->a_layout == T3_A_KM, s);
     if (st != T3_OK) return st;
   }
   if (track_copy)
@@ -566,7 +572,7 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
   q.R = C;   // the GEMM kernel's output pointer, addressed with ldc
-  return launch_gemm<t3k::kModeGemm>(q, tm, tn, p->b_layout == T3_B_KN,
+  return launch_gemm<t3k::kModeGemm>(q, tm, tn, p->b_layout == T3_B_KN, p->a_layout == T3_A_KM,
                                      static_cast<hipStream_t>(stream));
 }
 

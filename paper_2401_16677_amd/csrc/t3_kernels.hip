@@ -361,20 +361,20 @@ constexpr int kRPC = 8;               // rows filled by one 1-KiB copy
 // sched_group_barrier masks
 constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100;
 
-// Instruction order of one MFMA k-step: the operand reads of each of its MH row passes
-// (EXTRA more reads in the first), each followed by that pass's FMH * FN products.
-template <int MH, int FMH, int FN, int EXTRA>
+// Instruction order of one MFMA k-step: the operand reads of each of its MH row passes (AREADS
+// for the row blocks; FN + EXTRA more in the first), each followed by that pass's FMH * FN products.
+template <int MH, int FMH, int FN, int EXTRA, int AREADS = FMH>
 __device__ inline void sched_kstep() {
-  __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH + FN + EXTRA, 0);
+  __builtin_amdgcn_sched_group_barrier(kSchedDsRead, AREADS + FN + EXTRA, 0);
   __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
   if constexpr (MH >= 2) {
-    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, AREADS, 0);
     __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
   }
   if constexpr (MH == 4) {
-    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, AREADS, 0);
     __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
-    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, FMH, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, AREADS, 0);
     __builtin_amdgcn_sched_group_barrier(kSchedMfma, FMH * FN, 0);
   }
 }
@@ -427,7 +427,12 @@ constexpr int kRingSlots = 4;         // 1-KiB LDS slots per wavefront for trans
 // receives, for n = i, the values of the block's 4 k-rows.  32-byte pieces of a k-row sit at
 // position (piece ^ sw(k)), sw(k) = (k & 3) | ((k >> 3) & 1) << 2, which spreads the 8 k-rows
 // that 32 lanes read together over all banks.  K must be a multiple of 64 in this layout.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE, int BKN>
+//
+// AKM = 1: A is stored K x M with M contiguous (the transposed operand of the backward-pass
+// GEMMs, Sec. 5.2): the same arrangement on the A side -- its stage region holds 64 k-rows of BM
+// values, pieces swizzled the same way, operands fetched with the transposing read.  K must be
+// a multiple of 64 and M a multiple of 8.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE, int BKN, int AKM = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
 __attribute__((amdgpu_waves_per_eu((BM / WAVES_M) * (BN / WAVES_N) > 8192 ? 1 : 2)))
 void gemm_tile_kernel(const Plan p) {
@@ -452,7 +457,7 @@ void gemm_tile_kernel(const Plan p) {
 
   // Four wavefronts of 128 x 128 (one per SIMD) run the hand-ordered main loop and add the
   // incoming partial on the way out; B stored N x K only.
-  constexpr bool kAsmLoop = (NW == 4 && FM == 8 && FN == 8 && NSTAGE == 2 && !BKN);
+  constexpr bool kAsmLoop = (NW == 4 && FM == 8 && FN == 8 && NSTAGE == 2 && !BKN && !AKM);
   // Their pair transpositions get LDS of their own (4 KiB per wavefront) behind the stages.
   constexpr int kScrOff = kAsmLoop ? NSTAGE * kStageBytes : 0;
   static_assert(kScrOff + NW * kRingSlots * 1024 <= 160 * 1024, "LDS");
@@ -490,7 +495,7 @@ void gemm_tile_kernel(const Plan p) {
   const int part_slabs = (p.K / kBK) / p.split_k;
   const int k0 = part * part_slabs * kBK;
   const int Kpart = (part == p.split_k - 1) ? p.K - k0 : part_slabs * kBK;
-  const char *const Ap = (const char *)p.A + (int64_t)k0 * 2;
+  const char *const Ap = (const char *)p.A + (AKM ? (int64_t)k0 * p.lda * 2 : (int64_t)k0 * 2);
   const char *const Bp = (const char *)p.B + (BKN ? (int64_t)k0 * p.ldb * 2 : (int64_t)k0 * 2);
   Tile tl;
   int slot = 0, agent = 0;
@@ -528,10 +533,22 @@ void gemm_tile_kernel(const Plan p) {
   auto chunk_of = [&](int rows_per_wave, int q) {  // the k-chunk copy q of this lane fetches
     return (lane % kCPR) ^ swz(wave * rows_per_wave + q * kRPC + cp_row);
   };
+  constexpr int kARowBytes = BM * 2;             // (AKM) one k-row of the A region
+  constexpr int kSwMaskA = (BM / 16 < 8 ? BM / 16 : 8) - 1;
 #pragma unroll
   for (int q = 0; q < NA; ++q) {
-    const int r = wave * (BM / NW) + q * kRPC + cp_row;
-    offA[q] = (uint32_t)((min(m0 + r, p.M - 1) * p.lda + chunk_of(BM / NW, q) * 8) * 2);
+    if (AKM) {
+      // as for B stored K x N below: copy (wave * NA + q) fills 1 KiB of the A region, lane l
+      // lands in k-row L / kARowBytes at 16-byte position cp = half (cp & 1) of piece (cp >> 1) ^ sw(k)
+      const int L = (wave * NA + q) * 1024 + lane * 16;
+      const int k = L / kARowBytes, cp = (L % kARowBytes) / 16;
+      const int sw = ((k & 3) | (((k >> 3) & 1) << 2)) & kSwMaskA;
+      const int mcol = (((cp >> 1) ^ sw) * 2 + (cp & 1)) * 8;
+      offA[q] = (uint32_t)((k * p.lda + min(m0 + mcol, p.M - 8)) * 2);
+    } else {
+      const int r = wave * (BM / NW) + q * kRPC + cp_row;
+      offA[q] = (uint32_t)((min(m0 + r, p.M - 1) * p.lda + chunk_of(BM / NW, q) * 8) * 2);
+    }
   }
   constexpr int kBRowBytes = BN * 2;             // (BKN) one k-row of the B region
   constexpr int kSwMask = (BN / 16 < 8 ? BN / 16 : 8) - 1;
@@ -568,7 +585,7 @@ void gemm_tile_kernel(const Plan p) {
   auto issue_copies = [&](int kt, int stage, int q0, int q1) {
     kt += koff;                                   // slab kt of this workgroup's walk over K
     if (kt >= nkf) kt -= nkf;
-    const char *a = Ap + (int64_t)kt * (kBK * 2);
+    const char *a = Ap + (AKM ? (int64_t)kt * kBK * p.lda * 2 : (int64_t)kt * (kBK * 2));
     const char *b = Bp + (BKN ? (int64_t)kt * kBK * p.ldb * 2 : (int64_t)kt * (kBK * 2));
     const uint32_t dst = lds_base + stage * kStageBytes;
 #pragma unroll
@@ -604,6 +621,8 @@ void gemm_tile_kernel(const Plan p) {
   // (wn WN / 16 + j) ^ sw
   const int trB = kBOff + (8 * fq + (fr >> 2)) * kBRowBytes + (fr & 3) * 8;
   const int trSw = ((fr >> 2) | ((fq & 1) << 2)) & kSwMask;
+  const int trA = (8 * fq + (fr >> 2)) * kARowBytes + (fr & 3) * 8;        // (AKM) the same for A
+  const int trSwA = ((fr >> 2) | ((fq & 1) << 2)) & kSwMaskA;
 
   // NSTAGE-1 slabs are always in flight.  Past the last slab the copies are repeated into
   // stages nobody reads any more, so every wait below is for the same number of younger copies.
@@ -797,8 +816,21 @@ void gemm_tile_kernel(const Plan p) {
   auto read_u = [&](int u, int stage_off) {
     const int kk = u / MH, h = u % MH;
 #pragma unroll
-    for (int i = 0; i < FMH; ++i)
-      fa[u & 1][i] = *(const bf16x8 *)(lds + stage_off + fragA[kk] + (h * FMH + i) * 16 * kRowBytes);
+    for (int i = 0; i < FMH; ++i) {
+      if (AKM) {
+        typedef __attribute__((ext_vector_type(4))) short s16x4;
+        typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+        const char *a0 = lds + stage_off + trA + 32 * kk * kARowBytes +
+                         (((wm * (WM / 16) + h * FMH + i) ^ trSwA) << 5);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_void_ptr)a0);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_void_ptr)(a0 + 4 * kARowBytes));
+        typedef __attribute__((ext_vector_type(8))) short s16x8;
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        fa[u & 1][i] = __builtin_bit_cast(bf16x8, both);
+      } else {
+        fa[u & 1][i] = *(const bf16x8 *)(lds + stage_off + fragA[kk] + (h * FMH + i) * 16 * kRowBytes);
+      }
+    }
     if (h == 0) {
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
@@ -861,13 +893,13 @@ void gemm_tile_kernel(const Plan p) {
         issue_copies(kt_next, st_next, u * NL / MH, (u + 1) * NL / MH);
         mfma_u((u + US - 1) % US);                 // u == 0: last micro-step of slab kt-1
       }
-      sched_kstep<MH, FMH, FN, BKN ? FN : 0>();   // (the transposing reads are two per column block)
+      sched_kstep<MH, FMH, FN, BKN ? FN : 0, AKM ? 2 * FMH : FMH>();   // (the transposing reads are two per block)
 #pragma unroll
       for (int u = MH; u < US; ++u) {              // k-step 1
         read_u(u, so);
         mfma_u(u - 1);
       }
-      sched_kstep<MH, FMH, FN, BKN ? FN : 0>();   // (the transposing reads are two per column block)
+      sched_kstep<MH, FMH, FN, BKN ? FN : 0, AKM ? 2 * FMH : FMH>();   // (the transposing reads are two per block)
       stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     }
     mfma_u(US - 1);
@@ -883,6 +915,7 @@ void gemm_tile_kernel(const Plan p) {
     const uint4 zero = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
+      if (AKM) break;                              // (no ragged K in this layout)
       uint4 v = zero;
       if (chunk_of(BM / NW, q) * 8 < ktail) v = *(const uint4 *)(Ap + kb + offA[q]);
       *(uint4 *)(lds + ldsA_w + q * 1024 + lane * 16) = v;

@@ -14,7 +14,7 @@ def to_dev_bits(bits):
 
 
 def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfused=False,
-            ldr_pad=0, lda_pad=0, tile_begin=0, b_kn=False):
+            ldr_pad=0, lda_pad=0, tile_begin=0, b_kn=False, a_km=False):
     """One call of the fused path (or the unfused GEMM-then-reduce pair).  Returns a dict
     with R, fwd (uint16 bit patterns under T3_FLAG_FWD_BF16), counter, ready, queue, queue_len
     (numpy) and, for unfused, C."""
@@ -34,6 +34,11 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
         ldb = N + lda_pad
         b_host = np.zeros((K, ldb), dtype=np.uint16)
         b_host[:, :N] = np.ascontiguousarray(b_bits.T)
+    lda = K + lda_pad
+    if a_km:                       # the same A, stored K x M (M contiguous), rows padded by lda_pad
+        lda = M + lda_pad
+        a_host = np.zeros((K, lda), dtype=np.uint16)
+        a_host[:, :M] = np.ascontiguousarray(a_bits.T)
     A, B = to_dev_bits(a_host), to_dev_bits(b_host)
     ldr = N + ldr_pad
     R = torch.full((max(M, 1), ldr), 123.0, dtype=torch.float32, device=dev)
@@ -47,8 +52,9 @@ def run_gpu(a_bits, b_bits, inc, tp, rank, tile, *, flags=0, tile_limit=-1, unfu
         fwd = torch.full((max(tp - 1, 1), max(M, 1), max(W, 1)), SENTINEL, dtype=torch.float32,
                          device=dev)
     track = torch.full((t3.t3_track_words(tp),), 0x5A5A5A5A, dtype=torch.int32, device=dev)
-    p = t3.problem(M, N, K, tp, rank, tile[0], tile[1], lda=K + lda_pad, ldb=ldb,
+    p = t3.problem(M, N, K, tp, rank, tile[0], tile[1], lda=lda, ldb=ldb,
                    b_layout=t3.T3_B_KN if b_kn else t3.T3_B_NK,
+                   a_layout=t3.T3_A_KM if a_km else t3.T3_A_MK,
                    ldr=ldr, ldc=N, tile_limit=tile_limit, flags=flags, tile_begin=tile_begin)
     t3.t3_track_reset(tp, track)
     out = {}

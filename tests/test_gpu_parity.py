@@ -109,6 +109,41 @@ def test_b_stored_k_by_n_bit_exact(gpu, oracle, case, unfused, direct):
         assert np.array_equal(got["C"], oracle.gemm_rows(a, b).astype(np.float32))
 
 
+KM_CASES = [
+    # M,   N,    K,   tp, rank, tile          (K a multiple of 64, M a multiple of 8)
+    (256, 1024, 256, 4, 0, (128, 128)),
+    (304, 832, 192, 4, 2, (128, 128)),
+    (520, 1072, 128, 2, 1, (256, 128)),
+    (264, 1200, 320, 3, 0, (128, 256)),
+    (600, 1296, 1216, 2, 0, (256, 256)),
+    (512, 2048, 64, 4, 3, (256, 256)),
+]
+
+
+@pytest.mark.parametrize("b_kn", [False, True])
+@pytest.mark.parametrize("mode", ["fused_direct", "fused_copy", "unfused_direct"])
+@pytest.mark.parametrize("case", KM_CASES)
+def test_a_stored_k_by_m_bit_exact(gpu, oracle, case, mode, b_kn):
+    """A stored K x M, M contiguous (the transposed operand of the backward-pass GEMMs, Sec. 5.2),
+    with B in either layout: same results as with the M x K storage, every tile shape, ragged M
+    and W, padded leading dimensions."""
+    M, N, K, tp, rank, tile = case
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1700 + M)
+    direct, unfused = mode.endswith("direct"), mode.startswith("unfused")
+    print(f"case={case} mode={mode} b_kn={b_kn}", flush=True)
+    want = oracle.fused_path(np.ascontiguousarray(a.T), np.ascontiguousarray(b.T) if b_kn else b, inc, tp, rank,
+                             *tile, a_layout=oracle.A_KM, b_layout=oracle.B_KN if b_kn else oracle.B_NK,
+                             fwd_direct=direct,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=_flags(False, direct), unfused=unfused,
+                      lda_pad=8, b_kn=b_kn, a_km=True)
+    assert np.array_equal(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"])
+    _check_ints(got, want, tp, want["own"])
+    if unfused:
+        assert np.array_equal(got["C"], oracle.gemm_rows(a, b).astype(np.float32))
+
+
 @pytest.mark.parametrize("direct", [False, True])
 @pytest.mark.parametrize("case", EXACT_CASES[:4])
 def test_unfused_baseline_bit_exact(gpu, oracle, case, direct):
@@ -737,6 +772,36 @@ def test_full_size_b_stored_k_by_n(gpu, oracle):
             for s, c in enumerate(int(x) for x in order)]
     print(f"max normwise error over chunks {max(errs):.3e}", flush=True)
     assert max(errs) <= EXPECT
+
+
+@pytest.mark.parametrize("b_kn", [False, True])
+def test_full_size_a_stored_k_by_m(gpu, oracle, b_kn):
+    """gpt3_outproj at full size with A stored K x M (and B in either layout), direct release:
+    every element against the oracle."""
+    import torch
+    w = wl.WORKLOADS["gpt3_outproj"]
+    a, b, inc, S = _full_oracle(oracle, "gpt3_outproj")
+    dev = torch.device("cuda:0")
+    A = gpu.to_dev_bits(np.ascontiguousarray(a.T))
+    B = gpu.to_dev_bits(np.ascontiguousarray(b.T) if b_kn else b)
+    R = torch.from_numpy(inc).to(dev)
+    fwd = torch.full((w.tp - 1, w.M, w.W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(w.tp), dtype=torch.int32, device=dev)
+    p = t3.problem(w.M, w.N, w.K, w.tp, w.rank, w.tile_m, w.tile_n, a_layout=t3.T3_A_KM,
+                   b_layout=t3.T3_B_KN if b_kn else t3.T3_B_NK, flags=t3.T3_FLAG_FWD_DIRECT)
+    t3.t3_track_reset(w.tp, track)
+    t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+    torch.cuda.synchronize()
+    order, own = oracle.chunk_order(w.tp, w.rank)
+    tr = t3.read_track(track, w.tp)
+    assert np.all(tr["ready"] == 1) and tr["queue_len"] == w.tp - 1 and tr["error"] == 0
+    Rg, fg, W = R.cpu().numpy(), fwd.cpu().numpy(), w.W
+    scale = float(np.abs(S).max())
+    for s_, c in enumerate(int(x) for x in order):
+        got = Rg[:, c * W:(c + 1) * W] if c == own else fg[s_]
+        want = S[:, c * W:(c + 1) * W]
+        assert gpu.rel_err(got, want) <= EXPECT
+        assert float(np.abs(got.astype(np.float64) - want).max()) <= 1e-4 * scale
 
 
 @pytest.mark.parametrize("direct", [True, False])

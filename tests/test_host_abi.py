@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_problem_struct_matches_header_layout():
     # 8 int32, 5 int64, 1 uint32 (+ padding to 8), 1 int64, 2 int32
-    assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8 + 8 + 8
+    assert ctypes.sizeof(t3.T3Problem) == 8 * 4 + 5 * 8 + 8 + 8 + 8 + 8
     assert t3.T3Problem.split_k.offset == 88 and t3.T3Problem.upstream_agents.offset == 92
     assert t3.T3Problem.lda.offset == 32 and t3.T3Problem.flags.offset == 72
     assert t3.T3Problem.tile_begin.offset == 80
@@ -98,6 +98,14 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert _fused_status(t3.problem(**{**ok, "K": 200}, b_layout=t3.T3_B_KN)) == t3.T3_ERR_UNSUPPORTED
     assert _fused_status(t3.problem(**{**ok, "N": 1008}, b_layout=t3.T3_B_KN)) == t3.T3_ERR_ALIGN  # W = 252
     assert _fused_status(t3.problem(**ok, b_layout=t3.T3_B_KN, ldb=512)) == t3.T3_ERR_BAD_SHAPE
+    # A stored K x M: whole K-slabs of 64 only, M a multiple of 8, lda >= M, a known layout
+    assert _fused_status(t3.problem(**{**ok, "K": 200}, a_layout=t3.T3_A_KM)) == t3.T3_ERR_UNSUPPORTED
+    assert _fused_status(t3.problem(**{**ok, "M": 252}, a_layout=t3.T3_A_KM, lda=256)) == t3.T3_ERR_ALIGN
+    assert _fused_status(t3.problem(**ok, a_layout=t3.T3_A_KM, lda=248)) == t3.T3_ERR_BAD_SHAPE
+    assert _fused_status(t3.problem(**ok, a_layout=2)) == t3.T3_ERR_BAD_SHAPE
+    bad = t3.problem(**ok)
+    bad.reserved = 1
+    assert _fused_status(bad) == t3.T3_ERR_BAD_SHAPE
     assert _fused_status(t3.problem(**ok, b_layout=7)) == t3.T3_ERR_BAD_SHAPE
     # R of 4 GiB or more (32-bit byte offsets in the kernels): refused, nothing launched
     big = dict(M=65536, N=16384, K=64, tp=4, rank=0, tile_m=256, tile_n=256)
