@@ -236,20 +236,27 @@ __device__ inline u32x4 pack_bf16(f32x4 lo, f32x4 hi) {
 // Rows r0, r0 + step, ... < r_end of chunk c of R into forward slot `slot`, one wavefront per
 // row, 16 bytes per lane: the copy a trigger starts (Sec. 4.2.2).  The slot holds fp32, or
 // bfloat16 under kFlagFwdBf16.
+__device__ inline f32x4 load_agent(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t row_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)row_off, kAuxSc1 | kAuxNt));
+}
 __device__ inline void copy_chunk_rows(const Plan &p, int slot, int c, int r0, int r_end, int step) {
   const int lane = threadIdx.x & 63;
+  // R is read with agent-scope loads: they see the producers' write-through stores, so no cache
+  // has to be invalidated first (which would cost every workgroup of the XCD its slabs in L2)
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.R, (uint32_t)p.M * (uint32_t)p.ldr * 4u);
+  const uint32_t col_off = (uint32_t)c * (uint32_t)p.W * 4u;
   if (p.flags & kFlagFwdBf16) {
     const int W8 = p.W >> 3;
     for (int r = r0; r < r_end; r += step) {
-      const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
+      const uint32_t row_off = (uint32_t)r * (uint32_t)p.ldr * 4u + col_off;
       u32x4 *dst = (u32x4 *)((uint16_t *)p.fwd + ((int64_t)slot * p.M + r) * p.W);
       for (int c0 = lane; c0 < W8; c0 += 2 * 64) {
         f32x4 v[4];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
           if (c0 + u * 64 < W8) {
-            v[2 * u] = __builtin_nontemporal_load(src + 2 * (c0 + u * 64));
-            v[2 * u + 1] = __builtin_nontemporal_load(src + 2 * (c0 + u * 64) + 1);
+            v[2 * u] = load_agent(rs, (uint32_t)(c0 + u * 64) * 32u, row_off);
+            v[2 * u + 1] = load_agent(rs, (uint32_t)(c0 + u * 64) * 32u + 16u, row_off);
           }
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -261,13 +268,13 @@ __device__ inline void copy_chunk_rows(const Plan &p, int slot, int c, int r0, i
   }
   const int W4 = p.W >> 2;
   for (int r = r0; r < r_end; r += step) {
-    const f32x4 *src = (const f32x4 *)(p.R + (int64_t)r * p.ldr + (int64_t)c * p.W);
+    const uint32_t row_off = (uint32_t)r * (uint32_t)p.ldr * 4u + col_off;
     f32x4 *dst = (f32x4 *)(p.fwd + ((int64_t)slot * p.M + r) * p.W);
     for (int c0 = lane; c0 < W4; c0 += 4 * 64) {
       f32x4 v[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        if (c0 + u * 64 < W4) v[u] = __builtin_nontemporal_load(src + c0 + u * 64);
+        if (c0 + u * 64 < W4) v[u] = load_agent(rs, (uint32_t)(c0 + u * 64) * 16u, row_off);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
         if (c0 + u * 64 < W4) __builtin_nontemporal_store(v[u], dst + c0 + u * 64);
@@ -337,8 +344,6 @@ __device__ inline void release_chunk(const Plan &p, int slot, int agent, uint32_
     if (threadIdx.x == 0) trk_workgroup_done(p, t);
     return;
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of R
-
   copy_chunk_rows(p, slot, c, agent * p.rows_per_agent + (int)(threadIdx.x >> 6),
                   min(p.M, (agent + 1) * p.rows_per_agent), (int)(blockDim.x >> 6));
   __builtin_amdgcn_s_waitcnt(kWaitAll);
