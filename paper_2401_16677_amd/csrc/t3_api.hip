@@ -140,9 +140,10 @@ bool tile_supported(int32_t tm, int32_t tn) {
 
 void default_tile(const t3_problem *p, int cus, int32_t *tm, int32_t *tn) {
   // Cheapest shape by (work padded up to whole tiles) x (how much slower than the 256 x 256
-  // tile the shape's main loop runs per flop) x (how far the tiles fall short of filling the
-  // chip's `cus` compute units).
-  static const double kSlower[kNumTileShapes] = {1.0, 1.28, 1.28, 1.45};
+  // tile the shape's main loop runs per product, measured) x (how far the tiles fall short of
+  // filling the chip's `cus` compute units).  128 x 256 tiles are computed in pairs, as 256 x 256
+  // workgroup tiles: they cost what those cost, padding of M to 256 rows included.
+  static const double kSlower[kNumTileShapes] = {1.0, 1.21, 1.0, 1.28};
   const int64_t W = p->N / p->tp;
   double best = -1.0;
   *tm = 128;
@@ -151,9 +152,11 @@ void default_tile(const t3_problem *p, int cus, int32_t *tm, int32_t *tn) {
     const int64_t Mt = ceil_div(p->M, kTileShapes[i].m), Wt = ceil_div(W, kTileShapes[i].n);
     const int64_t T = Mt * Wt * p->tp;
     if (T == 0) continue;
-    const double padded = (double)(Mt * kTileShapes[i].m) * (double)(Wt * kTileShapes[i].n) /
-                          ((double)p->M * (double)W);
-    const double score = padded * kSlower[i] * (T < cus ? (double)cus / (double)T : 1.0);
+    const bool paired = kTileShapes[i].m == 128 && kTileShapes[i].n == 256 && Mt > 1;
+    const int64_t rows = paired ? ceil_div(p->M, 256) * 256 : Mt * kTileShapes[i].m;
+    const int64_t groups = paired ? ceil_div(Mt, 2) * Wt * p->tp : T;     // workgroup tiles
+    const double padded = (double)rows * (double)(Wt * kTileShapes[i].n) / ((double)p->M * (double)W);
+    const double score = padded * kSlower[i] * (groups < cus ? (double)cus / (double)groups : 1.0);
     if (best < 0 || score < best) {
       best = score;
       *tm = kTileShapes[i].m;
