@@ -1,15 +1,20 @@
 // Device code of the fused sliced-GEMM + reduce-scatter-reduction path for gfx950 (CDNA4).
 //
-// A persistent workgroup of 8 wavefronts (4 for the smallest tile) produces BM x BN output
-// tiles with v_mfma_f32_16x16x32_bf16.  K-slabs of 64 bf16 of A and B are copied global -> LDS
-// without passing through registers (global_load_lds_dwordx4) into two or three stages, ahead
-// of the slab being multiplied; LDS rows are XOR-swizzled so that the MFMA operand reads are
-// bank-conflict free.
+// A persistent workgroup produces BM x BN output tiles with v_mfma_f32_16x16x32_bf16.  K-slabs of
+// 64 bf16 of A and B are copied global -> LDS without passing through registers
+// (global_load_lds_dwordx4) into two or three stages, ahead of the slab being multiplied; LDS
+// rows are XOR-swizzled so that the MFMA operand reads are bank-conflict free.
+//
+// The 256 x 256 tile (B stored N x K, A stored M x K) runs on four wavefronts of 128 x 128, one
+// per SIMD, with a hand-ordered main loop: every operand read and slab copy has its place
+// between the products.  The other shapes and layouts run on eight (or, 128 x 128, four)
+// wavefronts with a compiler-scheduled loop.
 //
 // The reduction of Sec. 4.3 of the T3 paper (op-and-store into the buffer that also receives
 // the upstream partial) is done by starting the accumulators from the incoming partial, so a
-// tile is read once at its start and written once at its end; both moves use full 128-byte
-// lines and are transposed to and from the accumulator layout through LDS.
+// tile is read once and written once; both moves use full 128-byte lines and are transposed to
+// and from the accumulator layout through LDS.  A persistent workgroup requests the next
+// tile's incoming partial right behind the current tile's stores.
 //
 // Included by t3_api.hip only.
 #pragma once
