@@ -30,7 +30,8 @@ CONFIGS = ["tiny_outproj", "gpt3_outproj", "gpt3_fc2", "wide_fc2", "hightp_outpr
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries under profiles/ (each scaled by the same
 # counter's reading of a plain copy; the file says how).  Not measured in this run.  Keyed by
 # (workload, release); a workload is listed only while the kernel is the one that was profiled.
-PROFILED_TRAFFIC_BYTES = {}
+PROFILED_TRAFFIC_BYTES = {("gpt3_outproj", "direct"): 631.0e6, ("gpt3_fc2", "direct"): 1314.2e6,
+                          ("wide_fc2", "direct"): 2278.1e6, ("hightp_outproj", "direct"): 1737.9e6}
 PROFILED_TRAFFIC_SOURCE = "profiles/fused_gemm_rs_<workload>_hbm_traffic.txt (transcribed, not measured in this run)"
 
 
@@ -232,6 +233,10 @@ def main():
                     help="for `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE, MFMA counters): launch "
                          "5 x [a plain device copy of the M x N fp32 buffer, the fused kernel, the "
                          "unfused GEMM and reduction] and exit")
+    ap.add_argument("--with-library-gemm", action="store_true",
+                    help="with --traffic-probe: also launch the vendor library's bf16 GEMM behind "
+                         "torch.matmul on the same A and B (bf16 output, no reduction), so that a "
+                         "counter run shows its counters beside this library's kernels")
     args = ap.parse_args()
     direct = args.release == "direct"
     if args.gpus != 1:
@@ -250,10 +255,13 @@ def main():
     if args.traffic_probe:
         # the copy (a known number of bytes each way) calibrates the counters; see profiles/
         fused, unfused = b.steps(direct)
+        a16, b16t = b.A.view(torch.bfloat16), b.B.view(torch.bfloat16).t()
         for _ in range(5):
             b.C.copy_(b.R)
             fused()
             unfused()
+            if args.with_library_gemm:
+                torch.matmul(a16, b16t)
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": w.name, "copy_bytes_each_way": 4 * w.M * w.N,
                           "launches": 5}))
