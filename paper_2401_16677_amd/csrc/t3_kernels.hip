@@ -876,7 +876,13 @@ void gemm_tile_kernel(const Plan p) {
   // copies spread over its row passes; k-step 1.
   constexpr int kWaitSlab = wait_vm((NSTAGE - 2) * NL);
   if (nkf > 0) {
-    __builtin_amdgcn_s_waitcnt(kWaitSlab);         // slab 0 (and the incoming partial) landed
+    // Slab 0 (and the incoming partial) landed -- and this wavefront's LDS accesses are done: the
+    // transposition of the incoming partial used the last stage as scratch, and the copies issued
+    // right after this barrier refill that stage.  A copy that finds its line in L1 can land
+    // within a hundred clocks, before a read or write still waiting in a busy LDS queue (two
+    // workgroups share the unit): the read then returns slab data, the late write ruins the slab.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);
     __builtin_amdgcn_s_barrier();
     if (MODE == kModeFused && pending_c >= 0) {    // (also older: the previous tile's stores)
       track_count(p, trk, pending_c, pending_n);

@@ -171,3 +171,20 @@ def test_tracked_tiles_of_128_rows_computed_in_pairs(gpu, oracle, rng_kind, dire
     assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
     assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
     _check_ints(got, want, want["own"])
+
+
+def test_incoming_partial_survives_a_busy_lds_queue(gpu, oracle):
+    """The 128 x 128 tile runs two workgroups per compute unit, so the LDS unit is busy while a
+    workgroup turns its incoming partial into the accumulator layout in the stage that the main
+    loop refills next; those LDS accesses must be complete before the refill is requested.  The
+    launch is repeated: what is checked depends on timing."""
+    tile, (M, N, K, tp, rank) = (128, 128), (2040, 9728, 520, 4, 3)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=77)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    for rep in range(12):
+        print(f"tile={tile} shape={(M, N, K, tp, rank)} repetition {rep}", flush=True)
+        got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT, ldr_pad=4, lda_pad=8)
+        assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+        assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    _check_ints(got, want, want["own"])
