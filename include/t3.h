@@ -136,6 +136,17 @@ typedef struct {
  * launch of the process) overrides the default (4 groups over 12 us), T3_STAGGER=0 turns it
  * off.  Results do not depend on it.  The number of persistent workgroups follows the
  * device's compute-unit count; the XCD grouping is applied on devices with 8 XCDs.
+ * Balanced tail: when the tiles of such a launch do not fill a whole number of rounds of the
+ * persistent workgroups and the last round would occupy at most half of them, each tile of
+ * that round is computed as two halves of K by two workgroups, the first at the start of the
+ * launch and the second at its end, the partial sums passing through the place the result
+ * goes to (R, C or the fp32 forward slot); the tile is counted when the second half has
+ * stored it.  Tiles and counters are the same as without it, and so are the results up to
+ * the order in which the K-slabs are added in fp32 (the partial sums are stored and reloaded
+ * as they are; the order differs between workgroups anyway).  It applies to whole-problem
+ * launches (no tile range) with A and B in their default layouts and K >= 512, not to
+ * bfloat16 forward slots written directly, and for t3_gemm not while its stream is being
+ * captured into a graph.
  *
  * Tracker state (Sec. 4.2): one caller-owned device array of t3_track_words(tp) uint32
  * words, cleared once by t3_track_reset().  It holds two banks of 3*tp + 2 words
@@ -149,6 +160,8 @@ typedef struct {
  *   [6tp+4]        gen         launches completed since the reset
  *   [6tp+5]        error       0, or 1 if a release workgroup gave up waiting for a chunk
  *                              (cannot happen in a launch that ran to completion)
+ * and by 256 words the kernels use between the two halves of a split tile (balanced tail,
+ * above); they are 0 whenever no launch is running.
  * A launch of t3_gemm_rs_fused / t3_rs_reduce works in bank gen & 1; its last workgroup
  * clears the other bank and increments gen.  So consecutive launches need no reset in
  * between, and after a launch has completed its results are in bank (gen - 1) & 1.  A

@@ -24,6 +24,7 @@ constexpr int kNumTileShapes = sizeof(kTileShapes) / sizeof(kTileShapes[0]);
 constexpr int kNumXcd = 8;            // the XCD grouping of decode_tile is written for 8 XCDs
 constexpr int kDefaultCus = 256;       // compute units of an MI355X (host-only plan queries assume it)
 constexpr int kMaxDevices = 64;
+constexpr int kTailMinSlabs = 8;       // K-slabs of 64 a tile needs before a balanced tail splits it
 // Matrix rate of one compute unit the start-up offsets are sized with: 4096 flop/clock at a
 // sustained ~1.5 GHz under load, in flop per nanosecond.
 constexpr double kCuFlopPerNs = 6.25e3;
@@ -74,7 +75,7 @@ t3_status device_facts(DeviceFacts *out) {
 // until the process ends).  Host code never uses the array's name as an address: the device
 // address is looked up once per device and kept.
 constexpr int kStaticMaxTp = T3_STATIC_MAX_TP;
-constexpr int kStaticTrackWords = 2 * (3 * kStaticMaxTp + 2) + 2;
+constexpr int kStaticTrackWords = 2 * (3 * kStaticMaxTp + 2) + 2 + t3k::kTailSlots;
 static __device__ __align__(256) uint32_t scratch[kStaticTrackWords];
 uint32_t *g_scratch_ptr[kMaxDevices];
 
@@ -98,6 +99,67 @@ t3_status static_track(uint32_t **out) {
     return T3_ERR_HIP;
   }
   return T3_OK;
+}
+
+// Flags of the tiles a balanced tail splits, for t3_gemm, which is given no tracker state to
+// keep them in: a few sets of flag words per device.  Two launches may share a set only one
+// after the other (the second half of a tile clears the flag the first half raised), so behind
+// every launch an event is recorded, and a launch that takes a set whose last user may still be
+// running is made to wait for that event first: a launch on the same stream would have waited
+// anyway, launches on more streams than there are sets get serialised.  A launch whose stream is
+// being captured runs without a balanced tail (a replayed graph would use the set while this
+// bookkeeping knows nothing of it).
+constexpr int kGemmTailSets = 8;
+static __device__ __align__(256) uint32_t gemm_tail_flags[kGemmTailSets * t3k::kTailSlots];
+struct GemmTail {
+  uint32_t *base = nullptr;              // device address of the current device's gemm_tail_flags
+  hipEvent_t done[kGemmTailSets] = {};   // recorded behind the last launch that used the set
+  hipStream_t stream[kGemmTailSets] = {};
+  bool used[kGemmTailSets] = {};
+  unsigned next = 0;
+};
+GemmTail g_gemm_tail[kMaxDevices];
+
+// Launches the plain GEMM `q` (balanced tail wanted) on stream s with a set of flags, or without
+// a balanced tail if no set can be had.  The whole sequence runs under the lock, so that the
+// event of a set always belongs to its last launch.
+template <typename LaunchFn>
+t3_status launch_with_gemm_tail(t3k::Plan &q, hipStream_t s, LaunchFn launch_fn) {
+  auto plain = [&]() {
+    (void)hipGetLastError();
+    q.tail_r = q.tail_q = 0;
+    q.tail_flags = nullptr;
+    return launch_fn(q);
+  };
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  int dev = 0;
+  if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone ||
+      hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return plain();
+  std::lock_guard<std::mutex> lock(g_facts_mutex);
+  GemmTail &g = g_gemm_tail[dev];
+  if (!g.base) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(gemm_tail_flags)) != hipSuccess || !ptr) return plain();
+    g.base = static_cast<uint32_t *>(ptr);
+  }
+  // the set this stream used last, else the next in turn
+  int set = -1;
+  for (int i = 0; i < kGemmTailSets; ++i)
+    if (g.used[i] && g.stream[i] == s) set = i;
+  if (set < 0) set = (int)(g.next++ % kGemmTailSets);
+  if (!g.used[set]) {
+    if (hipEventCreateWithFlags(&g.done[set], hipEventDisableTiming) != hipSuccess) return plain();
+  } else if (hipStreamWaitEvent(s, g.done[set], 0) != hipSuccess) {
+    return plain();
+  }
+  g.used[set] = true;
+  g.stream[set] = s;
+  q.tail_flags = g.base + set * t3k::kTailSlots;
+  const t3_status st = launch_fn(q);
+  // (a launch that failed used nothing; a record that fails leaves the older record in place)
+  if (st == T3_OK && hipEventRecord(g.done[set], s) != hipSuccess) (void)hipGetLastError();
+  return st;
 }
 
 // T3_STAGGER="groups,window_ns" from the environment, read once per process.
@@ -189,6 +251,9 @@ enum Need { kNeedAB = 1, kNeedR = 2, kNeedC = 4, kNeedFwd = 8, kNeedTrack = 16,
             kNeedTwoWriters = 32 /* the call exists only in two-writer mode */,
             kMayPair = 64 /* the call launches the tile kernel, which can compute 256 x 256
                              workgroup tiles under 128 x 256 tracked ones */ };
+
+// The flag words of a balanced tail in tracker state: behind the two banks, gen and error.
+inline uint32_t *tail_flags_in(uint32_t *track, int32_t tp) { return track + 2 * (3 * (int64_t)tp + 2) + 2; }
 
 // Validates everything and fills the plan.  *empty is set when there is nothing to launch.
 t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B, const float *C,
@@ -393,6 +458,25 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.k_groups = dev.xcds > 1 ? dev.xcds : 0;
   q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
   q.resident = (int32_t)resident;
+  // Balanced tail (see the kernels' work_item): persistent launches of the tile kernel over the
+  // whole issue order whose last round of grid positions would fill at most half the chip; every
+  // half needs a few K-slabs, and the partial sums pass through the fp32 destination (so not
+  // through bfloat16 forward slots), each element with one writer at a time.
+  q.tail_r = q.tail_q = 0;
+  q.tail_flags = nullptr;
+  const bool persistent = (need & kMayPair) && q.agents == 0 && !two_writers;
+  const bool bf16_direct = direct && (p->flags & T3_FLAG_FWD_BF16);
+  const bool default_layouts = p->b_layout == T3_B_NK && p->a_layout == T3_A_MK;
+  const bool tail_kernel = !(*tm == 128 && *tn == 256);   // (128 x 256 tiles that are not paired: none)
+  if (persistent && !bf16_direct && default_layouts && tail_kernel && T > resident && q.begin == 0 &&
+      q.limit == T_t && p->K / 64 >= kTailMinSlabs) {
+    const int64_t r = T % resident;
+    if (r > 0 && 2 * r <= resident && r <= t3k::kTailSlots) {
+      q.tail_r = (int32_t)r;
+      q.tail_q = (int32_t)(T / resident);
+      if (track) q.tail_flags = tail_flags_in(track, p->tp);   // (t3_gemm brings its own)
+    }
+  }
   return T3_OK;
 }
 
@@ -420,6 +504,26 @@ t3_status launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStre
   const bool persistent = q.agents == 0;
   const int64_t positions = (int64_t)q.total_blocks * (MODE == t3k::kModeFused ? q.split_k : 1);
   const dim3 grid((unsigned)(persistent && positions > q.resident ? q.resident : positions));
+  // A balanced tail (make_plan decides; operands in their default layouts only) takes the
+  // kernels' TAIL variants.  The 256 x 256 one of the plain GEMM is the fused kernel's, told to
+  // take no incoming partial and track nothing (the plain kernel's own does not fit the
+  // register file).
+  if constexpr (!BKN && !AKM) {
+    if (q.tail_r) {
+      if (tm == 256 && tn == 256) {
+        t3k::Plan g = q;
+        if (MODE == t3k::kModeGemm) {
+          g.flags = t3k::kFlagPlain;
+          g.ldr = q.ldc;                  // (R already is the output pointer)
+        }
+        return launch(t3k::gemm_tile_kernel<256, 256, 2, 2, 2, t3k::kModeFused, 0, 0, 1>, grid, dim3(256), s, g);
+      }
+      if (tm == 256 && tn == 128)
+        return launch(t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, 0, 0, 1>, grid, dim3(512), s, q);
+      if (tm == 128 && tn == 128)
+        return launch(t3k::gemm_tile_kernel<128, 128, 2, 2, 2, MODE, 0, 0, 1>, grid, dim3(256), s, q);
+    }
+  }
   // K-slabs of 64 everywhere.  256 x 256: 4 wavefronts of 128 x 128 (or 8 of 128 x 64), two 64-KiB stages; the
   // 256 x 128 and 128 x 256 tiles: 8 wavefronts of 64 x 64, three 48-KiB stages; one workgroup
   // per compute unit.  128 x 128: 4 wavefronts of 64 x 64, two 32-KiB stages, two workgroups.
@@ -512,7 +616,7 @@ t3_status t3_tile_of(const t3_problem *p, int64_t t, int32_t *s, int32_t *c, int
   return T3_OK;
 }
 
-int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 2 * (3ll * tp + 2) + 2; }
+int64_t t3_track_words(int32_t tp) { return tp < 1 ? 0 : 2 * (3ll * tp + 2) + 2 + t3k::kTailSlots; }
 
 t3_status t3_track_reset(int32_t tp, uint32_t *track, void *stream) {
   if (!track) return T3_ERR_NULL;
@@ -551,6 +655,7 @@ t3_status t3_gemm_rs_fused_static(const t3_problem *p, const void *A, const void
   st = static_track(&track);
   if (st != T3_OK) return st;
   q.track = track;
+  if (q.tail_r) q.tail_flags = tail_flags_in(track, p->tp);
   hipStream_t s = static_cast<hipStream_t>(stream);
   // the array keeps the last call's contents: every call starts from a cleared tracker
   st = launch(t3k::track_reset_kernel, dim3(1), dim3(256), s, track, (int)p->tp);
@@ -575,8 +680,10 @@ t3_status t3_gemm(const t3_problem *p, const void *A, const void *B, float *C, v
   if (st != T3_OK) return st;
   if (empty) return T3_OK;
   q.R = C;   // the GEMM kernel's output pointer, addressed with ldc
-  return launch_gemm<t3k::kModeGemm>(q, tm, tn, p->b_layout == T3_B_KN, p->a_layout == T3_A_KM,
-                                     static_cast<hipStream_t>(stream));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool b_kn = p->b_layout == T3_B_KN, a_km = p->a_layout == T3_A_KM;
+  auto go = [&](const t3k::Plan &plan) { return launch_gemm<t3k::kModeGemm>(plan, tm, tn, b_kn, a_km, s); };
+  return q.tail_r ? launch_with_gemm_tail(q, s, go) : go(q);
 }
 
 t3_status t3_rs_reduce(const t3_problem *p, const float *C, float *R, void *fwd,

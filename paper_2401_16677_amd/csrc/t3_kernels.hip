@@ -42,11 +42,13 @@ typedef const __attribute__((address_space(1))) void *global_void_ptr;
 constexpr int kThreads = 256;
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kSpinLimit = 1 << 22;   // polls of a release workgroup before it gives up
+constexpr int kTailSlots = 256;       // tiles a balanced tail can split (flag words behind the tracker state)
 
 constexpr uint32_t kFlagStep0StoreOnly = 1u;
 constexpr uint32_t kFlagFwdDirect = 2u;
 constexpr uint32_t kFlagTwoWriters = 4u;
 constexpr uint32_t kFlagFwdBf16 = 8u;
+constexpr uint32_t kFlagPlain = 0x100u;   // internal: the fused kernel runs as a plain GEMM into R (see `plain`)
 
 enum Mode { kModeGemm = 0, kModeFused = 1 };
 enum Role { kRoleNone = 0, kRoleTile = 1, kRoleRelease = 2 };
@@ -84,6 +86,12 @@ struct Plan {
   int32_t split_k;                     // >= 1: workgroups that share a tile, each taking a part of K (Sec. 7.7)
   int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
   int32_t k_groups;                    // > 1: workgroup w starts its K loop (w % k_groups) / k_groups of the way in
+  // Balanced tail (persistent launches): the last tail_r grid positions, which would keep only
+  // tail_r of the workgroups busy for a whole tile time, are each split into two halves of K
+  // (see work_item).  0: off.  tail_q = full rounds of the grid before them; tail_flags = one
+  // word per split tile, 0 between launches.
+  int32_t tail_r, tail_q;
+  uint32_t *tail_flags;
   uint32_t flags;
 };
 
@@ -184,6 +192,63 @@ __device__ inline int decode_block(const Plan &p, int b, Tile &tl, int &slot, in
   slot = max(0, p.P - p.lag) + rem / p.agents;
   agent = rem % p.agents;
   return slot <= p.P - 2 ? kRoleRelease : kRoleNone;
+}
+
+// The it-th piece of work of a persistent workgroup: grid position `blk`, part `part` of
+// `nparts` parts of K.  Without a balanced tail, workgroup w of G takes positions w, w + G, ...
+// (split-K: `split_k` consecutive positions share a tile).
+//
+// Balanced tail.  With T = q G + r positions, 0 < r <= G / 2, the last round would run r tiles on
+// r workgroups while the others idle.  Instead each of those r tiles is cut into two halves of
+// K.  Half the workgroups are "early": early workgroup number i < r computes the first half of
+// tile q G + i BEFORE its q whole tiles, starting from the incoming partial as any tile does,
+// and stores the partial sums where the tile's result belongs.  The others are "late": late
+// workgroup number i < r computes the second half AFTER its q whole tiles, starting from those
+// partial sums, and stores and counts the tile.  Each workgroup then has at most q + 1/2 tiles
+// of work, and the first half is q tile times old when the second half asks for it (a flag per
+// tile says it is there; see the wait in the kernel).
+//
+// Workgroups 0 .. r-1 are early, r .. 2r-1 late; the early workgroup of a tile has the lower
+// index: it was dispatched first and waits for nothing, so the late one's wait ends.  Early and
+// late workgroups run half a tile time apart for the whole launch, and every XCD has both kinds
+// (r is normally a multiple of 8, so the two halves of a tile even run on the same XCD): that
+// spread of phases measures 5 % faster than whole XCDs running early or late.
+template <int TAIL>
+__device__ inline bool work_item(const Plan &p, int it, int &blk, int &part, int &nparts) {
+  const int G = (int)gridDim.x, w = (int)blockIdx.x;
+  if (TAIL && p.tail_r) {
+    nparts = 1;
+    part = 0;
+    const bool early = w < p.tail_r;
+    const int i = early ? w : w - p.tail_r;
+    if (early) {
+      if (it == 0) {
+        blk = p.tail_q * G + i;
+        nparts = 2;
+        return true;
+      }
+      blk = w + (it - 1) * G;
+      return it <= p.tail_q;
+    }
+    if (it < p.tail_q) {
+      blk = w + it * G;
+      return true;
+    }
+    if (it == p.tail_q && !early && i < p.tail_r) {
+      blk = p.tail_q * G + i;
+      part = 1;
+      nparts = 2;
+      return true;
+    }
+    return false;
+  }
+  // (positions fit 31 bits, the launch code sees to that)
+  const uint32_t pos = (uint32_t)w + (uint32_t)it * (uint32_t)G;
+  if (pos >= (uint32_t)p.total_blocks * (uint32_t)p.split_k) return false;
+  blk = (int)(pos / (uint32_t)p.split_k);
+  part = (int)(pos - (uint32_t)blk * (uint32_t)p.split_k);
+  nparts = p.split_k;
+  return true;
 }
 
 // Phase offsets at start-up.  All workgroups of the first wave of tiles start together and would
@@ -442,7 +507,9 @@ constexpr int kRingSlots = 4;         // 1-KiB LDS slots per wavefront for trans
 // GEMMs, Sec. 5.2): the same arrangement on the A side -- its stage region holds 64 k-rows of BM
 // values, pieces swizzled the same way, operands fetched with the transposing read.  K must be
 // a multiple of 64 and M a multiple of 8.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE, int BKN, int AKM = 0>
+//
+// TAIL = 1: the variant that can balance the tail of a persistent launch (see work_item).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE, int BKN, int AKM = 0, int TAIL = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
 __attribute__((amdgpu_waves_per_eu((BM / WAVES_M) * (BN / WAVES_N) > 8192 ? 1 : 2)))
 void gemm_tile_kernel(const Plan p) {
@@ -479,8 +546,12 @@ void gemm_tile_kernel(const Plan p) {
   // deferred into the next tile: by the first barrier of that tile's main loop every
   // wavefront has waited for its stores (they are older than the slab copies waited for
   // there), so the acknowledgement wait costs nothing.
+  // (a balanced tail's variant of the fused kernel also serves the plain GEMM: kFlagPlain, no
+  // incoming partial, nothing tracked)
+  const bool plain = TAIL && MODE == kModeFused && (p.flags & kFlagPlain);
+  const bool tracked = MODE == kModeFused && !plain;
   Trk trk;
-  if (MODE == kModeFused) trk = trk_open(p);   // reads gen now; used when tiles are done
+  if (tracked) trk = trk_open(p);              // reads gen now; used when tiles are done
   if (p.stagger_groups > 1) stagger_start(p);
 
   const int tid = threadIdx.x;
@@ -489,22 +560,39 @@ void gemm_tile_kernel(const Plan p) {
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   int pending_c = -1;                          // chunk of a tile whose stores are issued but not counted
   int pending_n = 1;                           //   and the tracked tiles it covers
+  int pending_half = -1;                       // first half of a split tile whose stores are issued but not announced
+  // to be called after a barrier that every wavefront reached with its stores acknowledged
+  auto settle_pending = [&]() {
+    if (tracked && pending_c >= 0) track_count(p, trk, pending_c, pending_n);
+    // (relaxed, like the counting: what orders it behind the partial sums is that they were
+    // written through and acknowledged before the barrier; a release would write back the L2)
+    if (TAIL && pending_half >= 0 && threadIdx.x == 0)
+      __hip_atomic_store(&p.tail_flags[pending_half], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    pending_c = pending_half = -1;
+  };
   auto flush_pending = [&]() {
-    if (MODE == kModeFused && pending_c >= 0) track_tile(p, trk, pending_c, pending_n);
-    pending_c = -1;
+    if ((tracked && pending_c >= 0) || (TAIL && pending_half >= 0)) {
+      __builtin_amdgcn_s_waitcnt(kWaitAll);
+      __syncthreads();
+      settle_pending();
+    }
   };
 
   // The accumulators live across tiles: the hand-ordered kernel fills them with the NEXT tile's
   // incoming partial while the current tile's sums are on their way out (`have_in`).
   f32x4 acc[BM / WAVES_M / 16][BN / WAVES_N / 16];
   bool have_in = false;
-  for (int pos = blockIdx.x; pos < p.total_blocks * p.split_k; pos += gridDim.x) {
-  // split-K (two-writer mode only): `split_k` consecutive positions share a tile, part j taking
-  // K-slabs [j q, (j+1) q) of the K / 64 full ones, the last part also what is left over
-  const int blk = pos / p.split_k, part = pos - blk * p.split_k;
-  const int part_slabs = (p.K / kBK) / p.split_k;
+  for (int it = 0;; ++it) {
+  // Parts of K (split-K in two-writer mode; the two halves of a balanced tail's tiles): part j
+  // takes K-slabs [j q, (j+1) q) of the K / 64 full ones, the last part also what is left over
+  int blk, part, nparts;
+  if (!work_item<TAIL>(p, it, blk, part, nparts)) break;
+  const int part_slabs = (p.K / kBK) / nparts;
   const int k0 = part * part_slabs * kBK;
-  const int Kpart = (part == p.split_k - 1) ? p.K - k0 : part_slabs * kBK;
+  const int Kpart = (part == nparts - 1) ? p.K - k0 : part_slabs * kBK;
+  const bool half0 = TAIL && p.tail_r && nparts == 2 && part == 0;   // partial sums out, nothing counted
+  const bool half1 = TAIL && p.tail_r && nparts == 2 && part == 1;   // starts from those partial sums
+  const int tail_idx = blk - p.tail_q * (int)gridDim.x;
   const char *const Ap = (const char *)p.A + (AKM ? (int64_t)k0 * p.lda * 2 : (int64_t)k0 * 2);
   const char *const Bp = (const char *)p.B + (BKN ? (int64_t)k0 * p.ldb * 2 : (int64_t)k0 * 2);
   Tile tl;
@@ -518,6 +606,18 @@ void gemm_tile_kernel(const Plan p) {
       release_chunk(p, slot, agent, (uint32_t *)lds);
     }
     continue;
+  }
+  if (half1 && threadIdx.x == 0) {
+    // The first half was computed by a workgroup with a lower index as its first piece of work
+    // and waits for nothing, so this wait ends (normally at once: that was q tile times ago).
+    int spins = 0;
+    while (__hip_atomic_load(&p.tail_flags[tail_idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
+           ++spins < kSpinLimit)
+      __builtin_amdgcn_s_sleep(16);
+    if (tracked && spins >= kSpinLimit)
+      __hip_atomic_fetch_or(trk.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // (this workgroup is the flag's only reader: cleared for the next launch)
+    __hip_atomic_store(&p.tail_flags[tail_idx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();                             // the previous tile's epilogue is done with the LDS
 
@@ -642,12 +742,25 @@ void gemm_tile_kernel(const Plan p) {
   // ---- accumulators start from the incoming partial (fused) or zero.
   // Block (i, j), element e of this lane: row 16*i + (lane & 15), column 16*j + 4*(lane >> 4) + e
   // of the wavefront tile.  Per 16-byte access 4 lanes cover 64 contiguous bytes of a row.
-  const bool store_only = (MODE == kModeGemm) || ((p.flags & kFlagStep0StoreOnly) && tl.s == 0);
+  const bool store_only = (MODE == kModeGemm) || plain || ((p.flags & kFlagStep0StoreOnly) && tl.s == 0);
   const bool to_fwd = (MODE == kModeFused) && (p.flags & kFlagFwdDirect) && tl.c != p.own;
   // two writers (Sec. 4.1): the tile is ADDED into R with atomics, as the upstream update is
   const bool two_writers = (MODE == kModeFused) && (p.flags & kFlagTwoWriters);
   const int rw0 = m0 + wm * WM, cw0 = n0 + wn * WN;          // wavefront tile origin (uniform)
   const bool full = (rw0 + WM <= p.M) && (cw0 + WN <= col_hi);
+  // where the tile's result goes (uniform): R, C, or the chunk's forward slot
+  const float *out_base;
+  uint32_t ld_out;
+  int col_org;            // column the base's rows start at
+  if (to_fwd) {
+    ld_out = (uint32_t)p.W;
+    out_base = p.fwd + (int64_t)tl.s * p.M * p.W;
+    col_org = col_lo;
+  } else {
+    ld_out = (uint32_t)((MODE == kModeGemm) ? p.ldc : p.ldr);
+    out_base = p.R;
+    col_org = 0;
+  }
   // ---- "pairs".  Global accesses that touch half a 128-byte line per row (what one 16 x 16
   // block in the accumulator layout amounts to) run at a third of the rate of full lines, so
   // the incoming partial and the results move in units of one PAIR = two neighbouring blocks =
@@ -674,7 +787,7 @@ void gemm_tile_kernel(const Plan p) {
     return u;
   };
   const PairLane ul = pair_lane(lane);           // (for the loads just below; the epilogue recomputes it)
-  const int *u_row = ul.row, *u_col = ul.col, *u_acc = ul.acc;
+  const int *u_acc = ul.acc;
 
   constexpr int NPAIR = NBLK / 2;
   static_assert(FN % 2 == 0, "pairs");
@@ -691,21 +804,27 @@ void gemm_tile_kernel(const Plan p) {
   // into the accumulator layout, so that the products accumulate on top of it.  (The scratch is
   // the last stage, which no copy touches before the main loop's first barrier; the hand-ordered
   // kernel has scratch of its own.)
-  auto in_pairs_load = [&](int m_lo, int n_lo, int col_end, bool whole) {
-    const uint32_t ld_in = (uint32_t)p.ldr;
-    const __amdgpu_buffer_rsrc_t in_rsrc = make_rsrc(p.R, (uint32_t)p.M * ld_in * 4u);
+  // (AGENT: the data was written by another workgroup of this launch, with agent-scope stores,
+  // and is read with agent-scope loads; src / ld_in / org: the array, its leading dimension and
+  // the column its rows start at)
+  auto in_pairs_load = [&](auto AGENT, const PairLane &ul, const float *src, uint32_t ld_in, int org, int m_lo,
+                           int n_lo, int col_end, bool whole) {
+    const int *u_row = ul.row, *u_col = ul.col;
+    const __amdgpu_buffer_rsrc_t in_rsrc = make_rsrc(src, (uint32_t)p.M * ld_in * 4u);
     uint32_t in_l[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
-      in_l[h] = ((uint32_t)(m_lo + u_row[h]) * ld_in + (uint32_t)(n_lo + u_col[h])) * 4u;
+      in_l[h] = ((uint32_t)(m_lo + u_row[h]) * ld_in + (uint32_t)(n_lo - org + u_col[h])) * 4u;
 #pragma unroll
     for (int t = 0; t < NPAIR; ++t) {
       const int i = t / UJ, jj = t % UJ;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (whole || (m_lo + 16 * i + u_row[h] < p.M && n_lo + 32 * jj + u_col[h] < col_end))
-          v = load_stream(in_rsrc, in_l[h], ((uint32_t)(16 * i) * ld_in + (uint32_t)(32 * jj)) * 4u);
+        if (whole || (m_lo + 16 * i + u_row[h] < p.M && n_lo + 32 * jj + u_col[h] < col_end)) {
+          const uint32_t blk_off = ((uint32_t)(16 * i) * ld_in + (uint32_t)(32 * jj)) * 4u;
+          v = decltype(AGENT)::value ? load_agent(in_rsrc, in_l[h], blk_off) : load_stream(in_rsrc, in_l[h], blk_off);
+        }
         acc[i][2 * jj + h] = v;
       }
     }
@@ -726,8 +845,13 @@ void gemm_tile_kernel(const Plan p) {
   // A persistent workgroup of the hand-ordered kernel requests the NEXT tile's incoming partial
   // at the end of a tile's epilogue, right behind that tile's stores (`have_in`): the loads are
   // then on their way while the workgroup decodes its next position and requests its first slabs.
-  if (MODE == kModeFused && !store_only && !two_writers) {
-    if (!have_in) in_pairs_load(rw0, cw0, col_hi, full);
+  if (half1) {
+    // the second half of a split tile starts from the first half's partial sums, which sit
+    // where the result will go
+    in_pairs_load(std::true_type{}, ul, out_base, ld_out, col_org, rw0, cw0, col_hi, full);
+    in_pairs_transpose();
+  } else if (MODE == kModeFused && !store_only && !two_writers) {
+    if (!have_in) in_pairs_load(std::false_type{}, ul, p.R, (uint32_t)p.ldr, 0, rw0, cw0, col_hi, full);
     in_pairs_transpose();
   }
   have_in = false;
@@ -790,10 +914,8 @@ void gemm_tile_kernel(const Plan p) {
     kstep(set0, true_type{}, false_type{}, adA[1], adB[1], 0, 0);
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();                  // slab 1 visible
-    if (MODE == kModeFused && pending_c >= 0) {    // the previous tile's stores are acknowledged too:
-      track_count(p, trk, pending_c, pending_n);   //   every wavefront has just waited for vmcnt(0)
-      pending_c = -1;
-    }
+    settle_pending();                              // the previous tile's stores are acknowledged too:
+                                                   //   every wavefront has just waited for vmcnt(0)
     uint32_t so = 0;                               // byte offset of the stage that holds slab kt
     for (int kt = 0; kt < nkf - 2; ++kt) {
       const uint32_t sn = so ^ (uint32_t)kStageBytes;
@@ -884,10 +1006,7 @@ void gemm_tile_kernel(const Plan p) {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(kWaitSlab & kWaitLgkm0);
     __builtin_amdgcn_s_barrier();
-    if (MODE == kModeFused && pending_c >= 0) {    // (also older: the previous tile's stores)
-      track_count(p, trk, pending_c, pending_n);
-      pending_c = -1;
-    }
+    settle_pending();                              // (also older: the previous tile's stores)
     issue_slab(min(NSTAGE - 1, nkf - 1), NSTAGE - 1);
     read_u(0, 0);
 #pragma unroll
@@ -955,24 +1074,16 @@ void gemm_tile_kernel(const Plan p) {
   }
 
   // ---- epilogue: the tile leaves in whole 128-byte lines, agent-scope (write-through) stores
-  const float *out_base;  // uniform: R, C, or the chunk's forward slot
-  uint32_t ld_out;
-  int col_org;            // column the base's rows start at
-  if (to_fwd) {
-    ld_out = (uint32_t)p.W;
-    out_base = p.fwd + (int64_t)tl.s * p.M * p.W;
-    col_org = col_lo;
-  } else {
-    ld_out = (uint32_t)((MODE == kModeGemm) ? p.ldc : p.ldr);
-    out_base = p.R;
-    col_org = 0;
-  }
   if constexpr (kAsmLoop) {
     // Pair by pair through this wavefront's own 4 KiB of LDS: written in the accumulator layout,
     // read back linearly, stored 8 rows x 128 bytes per instruction.  (Two-writer mode and
     // bfloat16 forward slots written directly are served by the eight-wavefront kernel.)
     const __amdgpu_buffer_rsrc_t out_rsrc = make_rsrc(out_base, (uint32_t)p.M * ld_out * 4u);
     char *scr = lds + kScrOff + wave * (kRingSlots * 1024);
+    int lane_e = lane;                             // recomputed here rather than kept through the main loop
+    asm volatile("" : "+v"(lane_e));
+    const PairLane ue = pair_lane(lane_e);
+    const int *u_row = ue.row, *u_col = ue.col, *u_acc = ue.acc;
     uint32_t out_u[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
@@ -981,10 +1092,11 @@ void gemm_tile_kernel(const Plan p) {
     // its accumulator blocks are requested once this tile's sums have been stored
     bool next_in = false, next_full = false;
     int next_rw0 = 0, next_cw0 = 0, next_col_hi = 0;
-    if (MODE == kModeFused && p.split_k == 1 && pos + (int)gridDim.x < p.total_blocks) {
+    int blk_n, part_n, nparts_n;
+    if (MODE == kModeFused && !plain && work_item<TAIL>(p, it + 1, blk_n, part_n, nparts_n) && nparts_n == 1) {
       Tile tn;
       int slot_n = 0, agent_n = 0;
-      if (decode_block(p, pos + (int)gridDim.x, tn, slot_n, agent_n) == kRoleTile &&
+      if (decode_block(p, blk_n, tn, slot_n, agent_n) == kRoleTile &&
           !((p.flags & kFlagStep0StoreOnly) && tn.s == 0)) {
         next_in = true;
         next_col_hi = tn.c * p.W + p.W;
@@ -1001,7 +1113,7 @@ void gemm_tile_kernel(const Plan p) {
       *(f32x4 *)(slot + u_acc[1]) = acc[i][2 * jj + 1];
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane * 16);
+        const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane_e * 16);
         if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
           store_agent(out_rsrc, out_u[h], ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u, v);
       }
@@ -1012,7 +1124,7 @@ void gemm_tile_kernel(const Plan p) {
     // memory more than a burst of each)
     if (next_in) {
       __builtin_amdgcn_sched_barrier(0);
-      in_pairs_load(next_rw0, next_cw0, next_col_hi, next_full);
+      in_pairs_load(std::false_type{}, ue, p.R, (uint32_t)p.ldr, 0, next_rw0, next_cw0, next_col_hi, next_full);
     }
     have_in = next_in;
   } else if (to_fwd && (p.flags & kFlagFwdBf16)) {
@@ -1107,12 +1219,14 @@ void gemm_tile_kernel(const Plan p) {
   }
   }
 
-  if (MODE == kModeFused) {
-    if (nkf == 0) flush_pending();               // (no main loop ran: nothing was counted on the way)
+  if (nkf == 0) flush_pending();                 // (no main loop ran: nothing was settled on the way)
+  if (half0) {
+    pending_half = tail_idx;                     // announced once the stores are acknowledged
+  } else if (tracked) {
     pending_c = tl.c;
     pending_n = min(p.pair_m, p.Mt_t - tl.mi * p.pair_m);
   }
-  }  // grid positions
+  }  // pieces of work
   flush_pending();
 }
 
@@ -1234,9 +1348,10 @@ __global__ __launch_bounds__(kThreads) void release_ready_kernel(const Plan p) {
                   min(p.M, (agent + 1) * p.rows_per_agent), kThreads / 64);
 }
 
-// Clears tracker state: both banks (queue entries to empty, the rest to 0), gen and error to 0.
+// Clears tracker state: both banks (queue entries to empty, the rest to 0), gen, error and the
+// flags of split tiles to 0.
 __global__ void track_reset_kernel(uint32_t *track, int P) {
-  const int bank = 3 * P + 2, n = 2 * bank + 2;
+  const int bank = 3 * P + 2, n = 2 * bank + 2 + kTailSlots;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     const int j = i < 2 * bank ? i % bank : -1;
     track[i] = (j >= 2 * P && j < 3 * P) ? kEmpty : 0u;

@@ -188,3 +188,79 @@ def test_incoming_partial_survives_a_busy_lds_queue(gpu, oracle):
         assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
         assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
     _check_ints(got, want, want["own"])
+
+
+# Balanced tail: the tiles do not fill a whole number of rounds of the resident workgroups and
+# the last round would fill at most half of them, so each of its tiles is computed as two
+# halves of K by two workgroups, the partial sums passing through the tile's destination.
+# M, N, K, tp, rank: tiles = q * resident + r, 0 < r <= resident / 2; K has a ragged last slab.
+TAIL = {
+    (256, 256): (2040, 20480, 520, 5, 2),     # 8 x 16 x 5 = 640 = 2 x 256 + 128
+    (256, 128): (2040, 10240, 584, 5, 4),     # 8 x 16 x 5 = 640
+    (128, 256): (2040, 20480, 520, 5, 0),     # computed in pairs: 8 x 16 x 5 = 640 workgroup tiles
+    (128, 128): (2040, 9728, 520, 4, 3),      # 16 x 19 x 4 = 1216 = 2 x 512 + 192
+}
+
+
+def _workgroup_tiles(M, N, tp, tile):
+    tm = 256 if tile == (128, 256) else tile[0]
+    return (-(-M // tm)) * (-(-(N // tp) // tile[1])) * tp
+
+
+@pytest.mark.parametrize("mode", ["fused_direct", "unfused_direct", "fused_direct_step0"])
+@pytest.mark.parametrize("tile", sorted(TAIL))
+def test_balanced_tail_every_element(gpu, oracle, tile, mode):
+    M, N, K, tp, rank = TAIL[tile]
+    resident = CUS * (2 if tile == (128, 128) else 1)
+    T = _workgroup_tiles(M, N, tp, tile)
+    assert T > resident and 0 < T % resident <= resident // 2 and K // 64 >= 8
+    step0 = mode.endswith("step0")
+    print(f"tile={tile} shape={(M, N, K, tp, rank)} mode={mode} tiles={T}", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1300 + tile[0] + tile[1] // 2)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True, step0_store_only=step0,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    flags = t3.T3_FLAG_FWD_DIRECT | (t3.T3_FLAG_STEP0_STORE_ONLY if step0 else 0)
+    # two launches before the one that is checked: the flags of the split tiles must be back
+    # to zero after every launch
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=flags, unfused=mode.startswith("unfused"),
+                      ldr_pad=4, lda_pad=8, launches_before=2)
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    assert np.all(got["R_pad"] == 123.0)
+    if mode.startswith("unfused"):
+        assert np.array_equal(got["C"], oracle.gemm_rows(a, b).astype(np.float32))
+    _check_ints(got, want, want["own"])
+
+
+def test_balanced_tail_of_one_tile(gpu, oracle):
+    """513 tiles on 256 workgroups: one tile is split between two workgroups."""
+    tile, (M, N, K, tp, rank) = (256, 256), (6900, 4864, 520, 19, 7)
+    assert _workgroup_tiles(M, N, tp, tile) == 2 * CUS + 1
+    print(f"tile={tile} shape={(M, N, K, tp, rank)}", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1500)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT, launches_before=1)
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.array_equal(got["fwd"], want["fwd"]), _first_mismatch(got["fwd"], want["fwd"])
+    _check_ints(got, want, want["own"])
+
+
+def test_balanced_tail_float_every_element(gpu, oracle):
+    """Normally distributed inputs through a split tile: the two halves of K are summed in fp32
+    one after the other, as the unsplit K loop does."""
+    tile = (256, 256)
+    M, N, K, tp, rank = TAIL[tile]
+    w = wl.make_shape("tail", M, N, K, tp, rank, *tile, index=77)
+    a, b, inc = wl.make_inputs(w)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    scale = float(np.abs(want["fwd"]).max())
+    for name in ("R", "fwd"):
+        d = np.abs(got[name].astype(np.float64) - want[name])
+        print(f"{name}: max |diff| {d.max():.3e} (scale {scale:.3e}), normwise {gpu.rel_err(got[name], want[name]):.3e}",
+              flush=True)
+        assert d.max() <= 1e-4 * scale
+        assert gpu.rel_err(got[name], want[name]) <= 1e-5
+    _check_ints(got, want, want["own"])

@@ -39,8 +39,11 @@ def _run(case, flags, static, torch):
 def test_static_tracker_entry_matches_the_caller_tracker_entry(flags):
     import torch
     assert torch.cuda.is_available(), "needs a GPU"
-    # first a problem with many tiles per workgroup and 8 chunks, then a smaller one with 4
-    cases = [(2040, 12288, 200, 8, 3, (256, 256), 41), (300, 1024, 136, 4, 1, (128, 128), 42)]
+    # first a problem whose last round of tiles is split in halves of K (the flags between the
+    # halves live in the static array too), then one with many tiles per workgroup and 8 chunks,
+    # then a smaller one with 4
+    cases = [(2040, 20480, 520, 5, 2, (256, 256), 40), (2040, 12288, 200, 8, 3, (256, 256), 41),
+             (300, 1024, 136, 4, 1, (128, 128), 42)]
     for case in cases:
         print(f"case={case} flags={flags}", flush=True)
         R0, f0, tr0 = _run(case, flags, False, torch)
