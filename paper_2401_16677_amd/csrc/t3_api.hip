@@ -24,6 +24,8 @@ constexpr int kNumTileShapes = sizeof(kTileShapes) / sizeof(kTileShapes[0]);
 constexpr int kNumXcd = 8;            // the XCD grouping of decode_tile is written for 8 XCDs
 constexpr int kDefaultCus = 256;       // compute units of an MI355X (host-only plan queries assume it)
 constexpr int kMaxDevices = 64;
+constexpr int kNtMinK = 3072;          // K from which result stores take the streaming hint
+constexpr int64_t kMemorySideCacheBytes = 256ll << 20;
 constexpr int kTailMinSlabs = 8;       // K-slabs of 64 a tile needs before a balanced tail splits it
 // Matrix rate of one compute unit the start-up offsets are sized with: 4096 flop/clock at a
 // sustained ~1.5 GHz under load, in flop per nanosecond.
@@ -458,6 +460,13 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   q.k_groups = dev.xcds > 1 ? dev.xcds : 0;
   q.total_blocks = (int32_t)(T + (int64_t)q.agents * (p->tp - 1));
   q.resident = (int32_t)resident;
+  // Results leave the XCD's L2 at once (streaming hint) where that L2 is better spent on slabs
+  // of A and B: long K loops, or an output that the memory-side cache cannot hold anyway.
+  // Measured: -3 % on gpt3_fc2 and hightp_outproj, -1 % on wide_fc2, but +6 % on gpt3_outproj
+  // (short K loop, output within the memory-side cache), so not there; and not when release
+  // workgroups read R back.
+  q.nt_out = (q.agents == 0 && !two_writers &&
+              (p->K >= kNtMinK || 4ll * p->M * p->N > kMemorySideCacheBytes)) ? 1 : 0;
   // Balanced tail (see the kernels' work_item): persistent launches of the tile kernel over the
   // whole issue order whose last round of grid positions would fill at most half the chip; every
   // half needs a few K-slabs, and the partial sums pass through the fp32 destination (so not
@@ -505,18 +514,18 @@ t3_status launch_gemm_layout(const t3k::Plan &q, int32_t tm, int32_t tn, hipStre
   const int64_t positions = (int64_t)q.total_blocks * (MODE == t3k::kModeFused ? q.split_k : 1);
   const dim3 grid((unsigned)(persistent && positions > q.resident ? q.resident : positions));
   // A balanced tail (make_plan decides; operands in their default layouts only) takes the
-  // kernels' TAIL variants.  The 256 x 256 one of the plain GEMM is the fused kernel's, told to
-  // take no incoming partial and track nothing (the plain kernel's own does not fit the
-  // register file).
+  // kernels' TAIL variants.  The 256 x 256 one of the plain GEMM is cut from the fused kernel
+  // (TAIL = 2).
   if constexpr (!BKN && !AKM) {
     if (q.tail_r) {
       if (tm == 256 && tn == 256) {
-        t3k::Plan g = q;
         if (MODE == t3k::kModeGemm) {
-          g.flags = t3k::kFlagPlain;
+          t3k::Plan g = q;
+          g.flags = 0;
           g.ldr = q.ldc;                  // (R already is the output pointer)
+          return launch(t3k::gemm_tile_kernel<256, 256, 2, 2, 2, t3k::kModeFused, 0, 0, 2>, grid, dim3(256), s, g);
         }
-        return launch(t3k::gemm_tile_kernel<256, 256, 2, 2, 2, t3k::kModeFused, 0, 0, 1>, grid, dim3(256), s, g);
+        return launch(t3k::gemm_tile_kernel<256, 256, 2, 2, 2, t3k::kModeFused, 0, 0, 1>, grid, dim3(256), s, q);
       }
       if (tm == 256 && tn == 128)
         return launch(t3k::gemm_tile_kernel<256, 128, 4, 2, 3, MODE, 0, 0, 1>, grid, dim3(512), s, q);

@@ -48,7 +48,6 @@ constexpr uint32_t kFlagStep0StoreOnly = 1u;
 constexpr uint32_t kFlagFwdDirect = 2u;
 constexpr uint32_t kFlagTwoWriters = 4u;
 constexpr uint32_t kFlagFwdBf16 = 8u;
-constexpr uint32_t kFlagPlain = 0x100u;   // internal: the fused kernel runs as a plain GEMM into R (see `plain`)
 
 enum Mode { kModeGemm = 0, kModeFused = 1 };
 enum Role { kRoleNone = 0, kRoleTile = 1, kRoleRelease = 2 };
@@ -86,6 +85,7 @@ struct Plan {
   int32_t split_k;                     // >= 1: workgroups that share a tile, each taking a part of K (Sec. 7.7)
   int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
   int32_t k_groups;                    // > 1: workgroup w starts its K loop (w % k_groups) / k_groups of the way in
+  int32_t nt_out;                      // results leave with the streaming hint (hand-ordered kernel)
   // Balanced tail (persistent launches): the last tail_r grid positions, which would keep only
   // tail_r of the workgroups busy for a whole tile time, are each split into two halves of K
   // (see work_item).  0: off.  tail_q = full rounds of the grid before them; tail_flags = one
@@ -286,6 +286,13 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t by
 }
 __device__ inline void store_agent(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t blk_off, f32x4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)lane_off, (int)blk_off, kAuxSc1);
+}
+// (NT: with the streaming hint as well: the lines do not stay in the XCD's L2, where slabs of A
+// and B are better kept)
+template <bool NT>
+__device__ inline void store_agent_hint(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t blk_off, f32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)lane_off, (int)blk_off,
+                                         NT ? (kAuxSc1 | kAuxNt) : kAuxSc1);
 }
 __device__ inline f32x4 load_stream(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t blk_off) {
   return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)blk_off, kAuxNt));
@@ -509,6 +516,9 @@ constexpr int kRingSlots = 4;         // 1-KiB LDS slots per wavefront for trans
 // a multiple of 64 and M a multiple of 8.
 //
 // TAIL = 1: the variant that can balance the tail of a persistent launch (see work_item).
+// TAIL = 2: that variant of the fused kernel with the reduction and the tracking taken out: the
+// plain GEMM with a balanced tail (the plain kernel's own TAIL = 1 variant of the hand-ordered
+// loop does not fit the register file).
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int MODE, int BKN, int AKM = 0, int TAIL = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
 __attribute__((amdgpu_waves_per_eu((BM / WAVES_M) * (BN / WAVES_N) > 8192 ? 1 : 2)))
@@ -546,9 +556,18 @@ void gemm_tile_kernel(const Plan p) {
   // deferred into the next tile: by the first barrier of that tile's main loop every
   // wavefront has waited for its stores (they are older than the slab copies waited for
   // there), so the acknowledgement wait costs nothing.
-  // (a balanced tail's variant of the fused kernel also serves the plain GEMM: kFlagPlain, no
-  // incoming partial, nothing tracked)
-  const bool plain = TAIL && MODE == kModeFused && (p.flags & kFlagPlain);
+  // (TAIL == 2: the fused kernel's code run as a plain GEMM with a balanced tail -- no incoming
+  // partial, nothing tracked, output through R)
+  static_assert(TAIL != 2 || MODE == kModeFused, "the plain variant is cut from the fused kernel");
+  bool plain = false;
+  if constexpr (TAIL == 2) {
+    // always, but not known to the compiler: as compile-time facts (accumulators always start
+    // from zero, nothing tracked, no next tile's partial to request) they lead its register
+    // allocation of the hand-ordered loop to spill, as they do in the plain kernel itself
+    int yes = 1;
+    asm volatile("" : "+s"(yes));
+    plain = yes != 0;
+  }
   const bool tracked = MODE == kModeFused && !plain;
   Trk trk;
   if (tracked) trk = trk_open(p);              // reads gen now; used when tiles are done
@@ -1105,21 +1124,26 @@ void gemm_tile_kernel(const Plan p) {
         next_full = (next_rw0 + WM <= p.M) && (next_cw0 + WN <= next_col_hi);
       }
     }
+    auto store_pairs = [&](auto NT) {
 #pragma unroll
-    for (int t = 0; t < NPAIR; ++t) {
-      const int i = t / UJ, jj = t % UJ;
-      char *slot = scr + ((2 * t) & (kRingSlots - 1)) * 1024;
-      *(f32x4 *)(slot + u_acc[0]) = acc[i][2 * jj];
-      *(f32x4 *)(slot + u_acc[1]) = acc[i][2 * jj + 1];
+      for (int t = 0; t < NPAIR; ++t) {
+        const int i = t / UJ, jj = t % UJ;
+        char *slot = scr + ((2 * t) & (kRingSlots - 1)) * 1024;
+        *(f32x4 *)(slot + u_acc[0]) = acc[i][2 * jj];
+        *(f32x4 *)(slot + u_acc[1]) = acc[i][2 * jj + 1];
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane_e * 16);
-        if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
-          store_agent(out_rsrc, out_u[h], ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u, v);
+        for (int h = 0; h < 2; ++h) {
+          const f32x4 v = *(const f32x4 *)(slot + h * 1024 + lane_e * 16);
+          if (full || (rw0 + 16 * i + u_row[h] < p.M && cw0 + 32 * jj + u_col[h] < col_hi))
+            store_agent_hint<decltype(NT)::value>(out_rsrc, out_u[h],
+                                                  ((uint32_t)(16 * i) * ld_out + (uint32_t)(32 * jj)) * 4u, v);
+        }
+        // keep the scheduler from running many pairs ahead: it would park their values in registers
+        if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
       }
-      // keep the scheduler from running many pairs ahead: it would park their values in registers
-      if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
-    }
+    };
+    if (p.nt_out) store_pairs(std::true_type{});
+    else store_pairs(std::false_type{});
     // (after the last store, not between the stores: reads and writes that alternate cost the
     // memory more than a burst of each)
     if (next_in) {
