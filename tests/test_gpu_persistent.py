@@ -264,3 +264,64 @@ def test_balanced_tail_float_every_element(gpu, oracle):
         assert d.max() <= 1e-4 * scale
         assert gpu.rel_err(got[name], want[name]) <= 1e-5
     _check_ints(got, want, want["own"])
+
+
+def test_ready_flag_publishes_a_chunk_while_the_launch_runs(gpu):
+    """The publication contract of the tracker in the persistent direct mode: once ready[c] has
+    been observed, chunk c's forward slot holds its final contents, although the launch that
+    produces the other chunks is still running.  The host watches the tracker from a second
+    stream while a long launch runs; whenever a chunk has become ready its slot is copied aside
+    (device to device, behind the observation), and afterwards every copy must equal the slot
+    as the finished launch left it."""
+    import torch
+    M, N, K, tp, rank, tile = 4096, 12288, 16384, 8, 3, (256, 256)
+    W = N // tp
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(5)
+    A = (torch.randn((M, K), device=dev, generator=g) * K ** -0.25).to(torch.bfloat16)
+    B = (torch.randn((N, K), device=dev, generator=g) * K ** -0.25).to(torch.bfloat16)
+    R = torch.randn((M, N), device=dev, generator=g)
+    words = t3.t3_track_words(tp)
+    p = t3.problem(M, N, K, tp, rank, *tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    host = torch.zeros(words, dtype=torch.int32).pin_memory()
+    order = [(rank + s) % tp for s in range(tp)]
+    seen_early = 0
+    for attempt in range(3):
+        fwd = torch.full((tp - 1, M, W), gpu.SENTINEL, dtype=torch.float32, device=dev)
+        snap = torch.zeros_like(fwd)
+        track = torch.zeros(words, dtype=torch.int32, device=dev)
+        t3.t3_track_reset(tp, track)
+        torch.cuda.synchronize()
+        done = torch.cuda.Event()
+        t3.t3_gemm_rs_fused(p, A, B, R.clone(), fwd, track, stream=main)
+        done.record(main)
+        taken, early = set(), set()
+        for _ in range(20000):
+            finished = done.query()                 # before the observation: "early" is certain
+            with torch.cuda.stream(side):
+                host.copy_(track, non_blocking=True)
+            side.synchronize()
+            ready = host[tp:2 * tp].tolist()        # bank 0: the launch after a reset works there
+            for s in range(tp - 1):
+                if ready[order[s]] == 1 and s not in taken:
+                    with torch.cuda.stream(side):
+                        snap[s].copy_(fwd[s], non_blocking=True)
+                    taken.add(s)
+                    if not finished:
+                        early.add(s)
+            if finished:
+                break
+        torch.cuda.synchronize()
+        tr = t3.read_track(track, tp)
+        assert tr["error"] == 0 and tr["queue_len"] == tp - 1
+        print(f"attempt {attempt}: slots copied {sorted(taken)}, of them while the launch ran {sorted(early)}",
+              flush=True)
+        for s in sorted(taken):
+            assert torch.equal(snap[s], fwd[s]), f"slot {s} changed after its chunk was announced ready"
+        assert not bool((fwd == gpu.SENTINEL).all(dim=(1, 2)).any())
+        seen_early = max(seen_early, len(early))
+        if seen_early:
+            break
+    assert seen_early >= 1, "the host never caught a chunk ready before the launch ended"
