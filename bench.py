@@ -67,6 +67,76 @@ def cpu_baseline(w, a_bits, b_bits, inc, target_s=12.0):
                       f"fp64 GEMM + reduction in {dt:.2f} s"}
 
 
+def timeline_report(b, direct, torch, t3):
+    """The last of 30 back-to-back fused launches, and of 30 plain-GEMM launches, of the workload
+    with t3_timeline recording, after the usual settling; returns a text table (times in microseconds; medians over the
+    workgroups that had an i-th piece of work)."""
+    w = b.w
+    p = b.problem(direct)
+    items, wgs = t3.T3_TIMELINE_ITEMS, 512
+    fused, unfused = b.steps(direct)
+    b.settle(fused, 0.5)
+    lines = [f"workload {w.name} (M={w.M} N={w.N} K={w.K} TP={w.tp} rank {w.rank}), "
+             f"release={'direct' if direct else 'copy'}; device wall clock (100 MHz), microseconds"]
+    runs = {"fused kernel (t3_gemm_rs_fused)": lambda: t3.t3_gemm_rs_fused(p, b.A, b.B, b.R, b.fwd, b.track),
+            "plain GEMM (t3_gemm)": lambda: t3.t3_gemm(p, b.A, b.B, b.C)}
+    totals = {}
+    for label, call in runs.items():
+        # 30 launches back to back, all recording into the same entries: what is read afterwards
+        # is the last one's, taken in this kernel's own steady state (a launch that follows even
+        # a short idle gap runs 15-20 % slower)
+        st = torch.zeros(wgs * items * 4, dtype=torch.int64, device=b.A.device)
+        ms = []
+        for _ in range(60):
+            call()                                   # this kernel's own steady state first
+        for rec in (None, st):                       # 30 launches without recording, then 30 with
+            t3.t3_timeline(rec)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(30):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1) / 30)
+        t3.t3_timeline(None)
+        s = st.cpu().numpy().reshape(wgs, items, 4).astype(np.float64)
+        used = s[:, 0, 0] > 0
+        n_wg = int(used.sum())
+        s = s[used]
+        t0 = s[:, 0, 0].min()
+        valid = s[:, :, 3] > 0
+        rel = np.where(s > 0, (s - t0) / 100.0, np.nan)
+        end = np.nanmax(rel[:, :, 3], axis=1)
+        lines += ["", f"{label}: {n_wg} workgroups, launch spans {np.nanmax(end):.1f} us from the first piece taken "
+                      f"to the last results handed over; {1e3 * ms[1]:.1f} us per launch with recording, {1e3 * ms[0]:.1f} without",
+                  f"  {'piece':<7}{'workgroups':>11}{'taken at':>10}{'set-up':>9}{'main loop':>11}{'hand-over':>11}{'whole piece':>13}"]
+        per_piece = []
+        for i in range(items):
+            v = valid[:, i]
+            if not v.any():
+                continue
+            r = rel[v, i, :]
+            d = [np.median(r[:, 1] - r[:, 0]), np.median(r[:, 2] - r[:, 1]), np.median(r[:, 3] - r[:, 2]),
+                 np.median(r[:, 3] - r[:, 0])]
+            per_piece.append(d)
+            lines.append(f"  {i:<7}{int(v.sum()):>11}{np.median(r[:, 0]):>10.1f}{d[0]:>9.1f}{d[1]:>11.1f}{d[2]:>11.1f}{d[3]:>13.1f}")
+        xcd = np.arange(wgs)[used] % 8
+        lines.append("  last hand-over per XCD (workgroup index mod 8), median of its workgroups: " +
+                     "  ".join(f"{x}: {np.median(end[xcd == x]):.1f}" for x in range(8) if (xcd == x).any()))
+        totals[label] = per_piece
+    f, g = totals["fused kernel (t3_gemm_rs_fused)"], totals["plain GEMM (t3_gemm)"]
+    if f and g and len(f) == len(g):
+        lines += ["", "fused minus plain GEMM, per piece (set-up / main loop / hand-over / whole): " +
+                  "; ".join(f"{a[0] - c[0]:+.1f} / {a[1] - c[1]:+.1f} / {a[2] - c[2]:+.1f} / {a[3] - c[3]:+.1f}"
+                            for a, c in zip(f, g))]
+    lines += ["", "set-up = piece taken -> accumulators hold the incoming partial (fused) or zeros (plain); for tiles after a",
+              "workgroup's first the incoming partial was requested at the end of the previous piece's hand-over, so part of",
+              "its flight time shows there.  main loop = the K loop.  hand-over = results through LDS into write-through stores",
+              "(+ the request for the next tile's incoming partial); their acknowledgement overlaps the next piece."]
+    return "\n".join(lines)
+
+
 class Bench:
     """Device buffers of one workload and the timed steps over them."""
 
@@ -237,6 +307,11 @@ def main():
                     help="with --traffic-probe: also launch the vendor library's bf16 GEMM behind "
                          "torch.matmul on the same A and B (bf16 output, no reduction), so that a "
                          "counter run shows its counters beside this library's kernels")
+    ap.add_argument("--timeline", action="store_true",
+                    help="record where the time of one fused launch and of one plain-GEMM launch "
+                         "goes (t3_timeline: per workgroup and piece of work, the wall clock when "
+                         "the piece is taken, when the accumulators are set up, when the main loop "
+                         "is done and when the results have been handed over), print a table and exit")
     args = ap.parse_args()
     direct = args.release == "direct"
     if args.gpus != 1:
@@ -265,6 +340,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": w.name, "copy_bytes_each_way": 4 * w.M * w.N,
                           "launches": 5}))
+        return
+
+    if args.timeline:
+        print(timeline_report(b, direct, torch, t3))
         return
 
     main_rec = b.measure(direct)

@@ -249,7 +249,7 @@ t3_status t3_gemm_rs_fused(const t3_problem *p, const void *A, const void *B, fl
  *                           results in bank (gen - 1) & 1, gen == 1 after a launch that ran tiles)
  *
  * Limits: tp <= T3_STATIC_MAX_TP (T3_ERR_UNSUPPORTED beyond it); the array takes
- * 2 * (3 * T3_STATIC_MAX_TP + 2) + 2 words (under 2 KiB) on every device the library has run
+ * t3_track_words(T3_STATIC_MAX_TP) words (under 3 KiB) on every device the library has run
  * on, until the process ends.  Every call clears it first (a small fill kernel on `stream`)
  * and all calls on one device share it: calls that overlap on one device -- different
  * streams, or graph replays in flight together -- race on it and must be serialised by the
@@ -312,6 +312,28 @@ t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
  */
 t3_status t3_ag_step(const t3_problem *p, int32_t step, const float *upstream_R, int64_t ld_up,
                      float *R, void *stream);
+
+/*
+ * Where a launch's time goes (a measuring aid for Sec. 4.1's overlap: how much of a tile's time
+ * is reduction traffic and how much is matrix work).  While `stamps` is set, every launch of
+ * the tile kernel (t3_gemm_rs_fused, t3_gemm_rs_fused_static, t3_gemm), from any thread,
+ * records for workgroup w and its i-th piece of work (a tile, or half of one in a balanced
+ * tail), i < T3_TIMELINE_ITEMS, four readings of the device's 100 MHz wall clock at
+ * stamps[(w * T3_TIMELINE_ITEMS + i) * 4 + 0 .. 3]:
+ *   0  the piece was taken
+ *   1  the accumulators are set up: the incoming partial has arrived and is in place
+ *   2  the main loop (and a ragged end of K) is done
+ *   3  the results have been handed to the memory system (they are acknowledged later, while
+ *      the next piece starts) and the next tile's incoming partial has been requested
+ * Workgroups w >= words / (4 * T3_TIMELINE_ITEMS) record nothing, nor do the kernels that serve
+ * 256 x 256 tiles with B stored K x N, A stored K x M, two writers or bfloat16 slots written
+ * directly.  Entries a launch does not
+ * write keep what they held.  stamps: device memory, 8-byte aligned, that stays valid until
+ * the launches that were issued while it was set have finished; NULL switches recording off.
+ * Later launches overwrite earlier ones.
+ */
+#define T3_TIMELINE_ITEMS 16
+t3_status t3_timeline(uint64_t *stamps, int64_t words);
 
 const char *t3_status_string(t3_status s);
 

@@ -20,11 +20,12 @@ T3_FLAG_FWD_DIRECT = 2
 T3_FLAG_TWO_WRITERS = 4
 T3_FLAG_FWD_BF16 = 8
 T3_STATIC_MAX_TP = 64
+T3_TIMELINE_ITEMS = 16
 
 EXPORTS = ["t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
            "t3_track_words", "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
            "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static", "t3_ag_step",
-           "t3_status_string", "t3_last_hip_error"]
+           "t3_timeline", "t3_status_string", "t3_last_hip_error"]
 
 
 class T3Problem(ctypes.Structure):
@@ -73,6 +74,7 @@ def lib():
         L.t3_gemm_rs_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp]
         L.t3_gemm_rs_fused_static.argtypes = [pp, vp, vp, vp, vp, vp, vp]
         L.t3_ag_step.argtypes = [pp, i32, vp, i64, vp, vp]
+        L.t3_timeline.argtypes = [vp, i64]
         L.t3_gemm.argtypes = [pp, vp, vp, vp, vp]
         L.t3_rs_reduce.argtypes = [pp, vp, vp, vp, vp, vp]
         L.t3_upstream_update.argtypes = [pp, vp, vp, vp, vp]
@@ -83,7 +85,7 @@ def lib():
         for f in ("t3_chunk_order", "t3_default_tile", "t3_tiles_per_chunk", "t3_tile_of",
                   "t3_track_reset", "t3_gemm_rs_fused", "t3_gemm", "t3_rs_reduce",
                   "t3_upstream_update", "t3_release_chunks", "t3_gemm_rs_fused_static",
-                  "t3_ag_step"):
+                  "t3_ag_step", "t3_timeline"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -185,6 +187,14 @@ def t3_gemm_rs_fused_static(p, A, B, R, fwd, track_copy=None, stream=None):
 def t3_ag_step(p, step, upstream_R, R, ld_up=None, stream=None):
     _check(lib().t3_ag_step(ctypes.byref(p), step, _dptr(upstream_R), p.ldr if ld_up is None else ld_up,
                             _dptr(R), _stream(stream)), "t3_ag_step")
+
+
+def t3_timeline(stamps):
+    """stamps: an int64 device tensor (or None to switch recording off)."""
+    if stamps is None:
+        _check(lib().t3_timeline(None, 0), "t3_timeline")
+    else:
+        _check(lib().t3_timeline(_dptr(stamps), stamps.numel()), "t3_timeline")
 
 
 def t3_gemm(p, A, B, C, stream=None):

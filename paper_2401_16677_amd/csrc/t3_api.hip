@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <stdio.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "t3_kernels.hip"
@@ -71,6 +72,10 @@ t3_status device_facts(DeviceFacts *out) {
   }
   return T3_OK;
 }
+
+// Where tile kernels record their timelines (t3_timeline), for the launches of every thread.
+std::atomic<uint64_t *> g_timeline{nullptr};
+std::atomic<int64_t> g_timeline_wgs{0};
 
 // Tracker state for t3_gemm_rs_fused_static, the entry point for callers that cannot allocate:
 // one array per device (each GPU the library runs on holds its own copy at its own address
@@ -246,6 +251,7 @@ static_assert(T3_FLAG_STEP0_STORE_ONLY == t3k::kFlagStep0StoreOnly &&
                   T3_FLAG_TWO_WRITERS == t3k::kFlagTwoWriters && T3_FLAG_FWD_BF16 == t3k::kFlagFwdBf16,
               "flag bits of the header and of the kernels");
 static_assert(sizeof(t3_problem) == 104, "layout documented in the header");
+static_assert(T3_TIMELINE_ITEMS == t3k::kTimelineItems, "timeline layout of the header and of the kernels");
 
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
@@ -467,6 +473,11 @@ t3_status make_plan(const t3_problem *p, int need, const void *A, const void *B,
   // workgroups read R back.
   q.nt_out = (q.agents == 0 && !two_writers &&
               (p->K >= kNtMinK || 4ll * p->M * p->N > kMemorySideCacheBytes)) ? 1 : 0;
+  q.timeline = g_timeline.load();
+  {
+    const int64_t wgs = g_timeline_wgs.load();
+    q.timeline_wgs = (int32_t)(wgs > (1ll << 30) ? (1ll << 30) : wgs);
+  }
   // Balanced tail (see the kernels' work_item): persistent launches of the tile kernel over the
   // whole issue order whose last round of grid positions would fill at most half the chip; every
   // half needs a few K-slabs, and the partial sums pass through the fp32 destination (so not
@@ -752,6 +763,22 @@ t3_status t3_release_chunks(const t3_problem *p, const float *R, void *fwd,
   q.rows_per_agent = (int32_t)ceil_div(p->M, q.agents);
   return launch(t3k::release_ready_kernel, dim3((unsigned)(q.agents * (p->tp - 1))),
                 dim3(t3k::kThreads), static_cast<hipStream_t>(stream), q);
+}
+
+t3_status t3_timeline(uint64_t *stamps, int64_t words) {
+  if (stamps && words < 0) return T3_ERR_BAD_SHAPE;
+  if (stamps && (reinterpret_cast<uintptr_t>(stamps) & 7u)) return T3_ERR_ALIGN;
+  // (the count first when switching off, the pointer first when switching on: a launch planned
+  // in between records nothing rather than out of bounds)
+  if (!stamps) {
+    g_timeline.store(nullptr);
+    g_timeline_wgs.store(0);
+    return T3_OK;
+  }
+  g_timeline_wgs.store(0);
+  g_timeline.store(stamps);
+  g_timeline_wgs.store(words / (4 * T3_TIMELINE_ITEMS));
+  return T3_OK;
 }
 
 t3_status t3_ag_step(const t3_problem *p, int32_t step, const float *upstream_R, int64_t ld_up,

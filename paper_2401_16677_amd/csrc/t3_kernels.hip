@@ -42,6 +42,7 @@ typedef const __attribute__((address_space(1))) void *global_void_ptr;
 constexpr int kThreads = 256;
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kSpinLimit = 1 << 22;   // polls of a release workgroup before it gives up
+constexpr int kTimelineItems = 16;     // pieces of work per workgroup a timeline records
 constexpr int kTailSlots = 256;       // tiles a balanced tail can split (flag words behind the tracker state)
 
 constexpr uint32_t kFlagStep0StoreOnly = 1u;
@@ -86,6 +87,12 @@ struct Plan {
   int32_t stagger_blocks, stagger_groups, stagger_ticks;   // start-up phase offsets (see stagger_start)
   int32_t k_groups;                    // > 1: workgroup w starts its K loop (w % k_groups) / k_groups of the way in
   int32_t nt_out;                      // results leave with the streaming hint (hand-ordered kernel)
+  // Timeline (a profiling aid, normally null): workgroup w < timeline_wgs writes, for its i-th
+  // piece of work, i < kTimelineItems, four wall-clock readings (100 MHz) at
+  // timeline[(w * kTimelineItems + i) * 4 + ...]: piece taken; accumulators set up (the
+  // incoming partial in place); main loop done; results handed to the memory system.
+  uint64_t *timeline;
+  int32_t timeline_wgs;
   // Balanced tail (persistent launches): the last tail_r grid positions, which would keep only
   // tail_r of the workgroups busy for a whole tile time, are each split into two halves of K
   // (see work_item).  0: off.  tail_q = full rounds of the grid before them; tail_flags = one
@@ -597,6 +604,13 @@ void gemm_tile_kernel(const Plan p) {
     }
   };
 
+  // (not in the eight-wavefront 256 x 256 kernels: they have no register to spare)
+  constexpr bool kTimeline = !(NW == 8 && FM == 8);
+  auto stamp = [&](int it, int k) {
+    if (kTimeline && p.timeline && threadIdx.x == 0 && (int)blockIdx.x < p.timeline_wgs && it < kTimelineItems)
+      p.timeline[((size_t)blockIdx.x * kTimelineItems + it) * 4 + k] = wall_clock64();
+  };
+
   // The accumulators live across tiles: the hand-ordered kernel fills them with the NEXT tile's
   // incoming partial while the current tile's sums are on their way out (`have_in`).
   f32x4 acc[BM / WAVES_M / 16][BN / WAVES_N / 16];
@@ -606,6 +620,7 @@ void gemm_tile_kernel(const Plan p) {
   // takes K-slabs [j q, (j+1) q) of the K / 64 full ones, the last part also what is left over
   int blk, part, nparts;
   if (!work_item<TAIL>(p, it, blk, part, nparts)) break;
+  stamp(it, 0);
   const int part_slabs = (p.K / kBK) / nparts;
   const int k0 = part * part_slabs * kBK;
   const int Kpart = (part == nparts - 1) ? p.K - k0 : part_slabs * kBK;
@@ -874,6 +889,7 @@ void gemm_tile_kernel(const Plan p) {
     in_pairs_transpose();
   }
   have_in = false;
+  stamp(it, 1);
 
   if constexpr (kAsmLoop) {
   // ---- main loop, hand-ordered.  One wavefront per SIMD: nobody else fills the matrix pipe while
@@ -1092,6 +1108,7 @@ void gemm_tile_kernel(const Plan p) {
     }
   }
 
+  stamp(it, 2);
   // ---- epilogue: the tile leaves in whole 128-byte lines, agent-scope (write-through) stores
   if constexpr (kAsmLoop) {
     // Pair by pair through this wavefront's own 4 KiB of LDS: written in the accumulator layout,
@@ -1243,6 +1260,7 @@ void gemm_tile_kernel(const Plan p) {
   }
   }
 
+  stamp(it, 3);
   if (nkf == 0) flush_pending();                 // (no main loop ran: nothing was settled on the way)
   if (half0) {
     pending_half = tail_idx;                     // announced once the stores are acknowledged

@@ -325,3 +325,35 @@ def test_ready_flag_publishes_a_chunk_while_the_launch_runs(gpu):
         if seen_early:
             break
     assert seen_early >= 1, "the host never caught a chunk ready before the launch ended"
+
+
+def test_timeline_records_every_piece_and_changes_nothing(gpu, oracle):
+    """t3_timeline: with recording on, every workgroup leaves four non-decreasing clock readings
+    per piece of work (here 3 tiles per workgroup), the results are what they are without it,
+    and after switching it off nothing more is written."""
+    import torch
+    tile = (256, 256)
+    M, N, K, tp, rank = MULTI[tile]
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1600)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True,
+                             fwd_init=np.full((tp - 1, M, N // tp), gpu.SENTINEL, np.float32))
+    items = t3.T3_TIMELINE_ITEMS
+    st = torch.zeros(CUS * items * 4, dtype=torch.int64, device="cuda:0")
+    t3.t3_timeline(st)
+    try:
+        got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    finally:
+        t3.t3_timeline(None)
+    assert np.array_equal(got["R"], want["R"]) and np.array_equal(got["fwd"], want["fwd"])
+    _check_ints(got, want, want["own"])
+    s = st.cpu().numpy().reshape(CUS, items, 4)
+    pieces = (s[:, :, 0] > 0).sum(axis=1)
+    assert np.all(pieces == 3), pieces                       # 768 tiles on 256 workgroups
+    rec = s[:, :3, :]
+    assert np.all(rec > 0) and np.all(np.diff(rec, axis=2) >= 0)
+    assert np.all(rec[:, 1:, 0] >= rec[:, :-1, 3])           # a piece starts after the one before it
+    assert np.all(s[:, 3:, :] == 0)
+    before = st.clone()
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT)
+    assert torch.equal(st, before)
+    assert np.array_equal(got["fwd"], want["fwd"])
