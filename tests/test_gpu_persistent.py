@@ -357,3 +357,68 @@ def test_timeline_records_every_piece_and_changes_nothing(gpu, oracle):
     got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT)
     assert torch.equal(st, before)
     assert np.array_equal(got["fwd"], want["fwd"])
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+def test_balanced_tail_in_a_captured_graph(gpu, oracle, unfused):
+    """A problem with a balanced tail captured in a HIP graph and replayed: the fused call keeps
+    the flags between the halves of a tile in the tracker state, which the graph carries; the
+    plain GEMM of the unfused pair has none of its own and runs without a balanced tail while its
+    stream is being captured.  Every replay must reproduce the oracle, with eager launches of the
+    same calls (which do balance the tail) in between."""
+    import torch
+    tile = (256, 256)
+    M, N, K, tp, rank = TAIL[tile]
+    W = N // tp
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1700)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=True,
+                             fwd_init=np.zeros((tp - 1, M, W), np.float32))
+    dev = torch.device("cuda:0")
+    A, B = gpu.to_dev_bits(a), gpu.to_dev_bits(b)
+    inc_dev = torch.from_numpy(inc).to(dev)
+    R = inc_dev.clone()
+    C = torch.zeros((M, N), dtype=torch.float32, device=dev)
+    fwd = torch.zeros((tp - 1, M, W), dtype=torch.float32, device=dev)
+    track = torch.zeros(t3.t3_track_words(tp), dtype=torch.int32, device=dev)
+    p = t3.problem(M, N, K, tp, rank, *tile, flags=t3.T3_FLAG_FWD_DIRECT)
+
+    def step():
+        t3.t3_track_reset(tp, track)
+        if unfused:
+            t3.t3_gemm(p, A, B, C)
+            t3.t3_rs_reduce(p, C, R, fwd, track)
+        else:
+            t3.t3_gemm_rs_fused(p, A, B, R, fwd, track)
+
+    def check(what):
+        torch.cuda.synchronize()
+        own = want["own"]
+        assert np.array_equal(fwd.cpu().numpy(), want["fwd"]), what
+        assert np.array_equal(R.cpu().numpy()[:, own * W:(own + 1) * W], want["owned"]), what
+        tr = t3.read_track(track, tp)
+        assert np.array_equal(tr["counter"], want["counter"]) and tr["queue_len"] == tp - 1, what
+        assert tr["error"] == 0, what
+
+    def restore():
+        R.copy_(inc_dev)
+        fwd.zero_()
+        C.fill_(3.0)
+        torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    check("eager, before capture")
+    restore()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        step()
+    for rep in range(3):
+        restore()
+        g.replay()
+        check(f"replay {rep}")
+        restore()
+        step()
+        check(f"eager after replay {rep}")
