@@ -30,8 +30,8 @@ CONFIGS = ["tiny_outproj", "gpt3_outproj", "gpt3_fc2", "wide_fc2", "hightp_outpr
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries under profiles/ (each scaled by the same
 # counter's reading of a plain copy; the file says how).  Not measured in this run.  Keyed by
 # (workload, release); a workload is listed only while the kernel is the one that was profiled.
-PROFILED_TRAFFIC_BYTES = {("gpt3_outproj", "direct"): 630.9e6, ("gpt3_fc2", "direct"): 1313.4e6,
-                          ("wide_fc2", "direct"): 2488.7e6, ("hightp_outproj", "direct"): 1737.4e6}
+PROFILED_TRAFFIC_BYTES = {("gpt3_outproj", "direct"): 630.8e6, ("gpt3_fc2", "direct"): 1314.0e6,
+                          ("wide_fc2", "direct"): 2492.1e6, ("hightp_outproj", "direct"): 1737.4e6}
 PROFILED_TRAFFIC_SOURCE = "profiles/fused_gemm_rs_<workload>_hbm_traffic.txt (transcribed, not measured in this run)"
 
 
