@@ -111,22 +111,33 @@ def timeline_report(b, direct, torch, t3):
         lines += ["", f"{label}: {n_wg} workgroups, launch spans {np.nanmax(end):.1f} us from the first piece taken "
                       f"to the last results handed over; {1e3 * ms[1]:.1f} us per launch with recording, {1e3 * ms[0]:.1f} without",
                   f"  {'piece':<7}{'workgroups':>11}{'taken at':>10}{'set-up':>9}{'main loop':>11}{'hand-over':>11}{'whole piece':>13}"]
+        # A balanced tail gives half the workgroups a half tile first and the others one last:
+        # the two kinds are tabulated apart (told by the length of the first piece).
+        first = rel[:, 0, 3] - rel[:, 0, 0]
+        groups = [("", np.ones(len(first), bool))]
+        if first.max() > 1.5 * first.min():
+            short = first < 0.5 * (first.max() + first.min())
+            groups = [("  workgroups that start with half a tile:", short), ("  the others:", ~short)]
         per_piece = []
-        for i in range(items):
-            v = valid[:, i]
-            if not v.any():
-                continue
-            r = rel[v, i, :]
-            d = [np.median(r[:, 1] - r[:, 0]), np.median(r[:, 2] - r[:, 1]), np.median(r[:, 3] - r[:, 2]),
-                 np.median(r[:, 3] - r[:, 0])]
-            per_piece.append(d)
-            lines.append(f"  {i:<7}{int(v.sum()):>11}{np.median(r[:, 0]):>10.1f}{d[0]:>9.1f}{d[1]:>11.1f}{d[2]:>11.1f}{d[3]:>13.1f}")
+        for title, sel in groups:
+            if title:
+                lines.append(title)
+            for i in range(items):
+                v = valid[:, i] & sel
+                if not v.any():
+                    continue
+                r = rel[v, i, :]
+                d = [np.median(r[:, 1] - r[:, 0]), np.median(r[:, 2] - r[:, 1]), np.median(r[:, 3] - r[:, 2]),
+                     np.median(r[:, 3] - r[:, 0])]
+                if len(groups) == 1:
+                    per_piece.append(d)
+                lines.append(f"  {i:<7}{int(v.sum()):>11}{np.median(r[:, 0]):>10.1f}{d[0]:>9.1f}{d[1]:>11.1f}{d[2]:>11.1f}{d[3]:>13.1f}")
         xcd = np.arange(wgs)[used] % 8
         lines.append("  last hand-over per XCD (workgroup index mod 8), median of its workgroups: " +
                      "  ".join(f"{x}: {np.median(end[xcd == x]):.1f}" for x in range(8) if (xcd == x).any()))
         totals[label] = per_piece
     f, g = totals["fused kernel (t3_gemm_rs_fused)"], totals["plain GEMM (t3_gemm)"]
-    if f and g and len(f) == len(g):
+    if f and g and len(f) == len(g):   # (not with a balanced tail: its pieces differ in kind)
         lines += ["", "fused minus plain GEMM, per piece (set-up / main loop / hand-over / whole): " +
                   "; ".join(f"{a[0] - c[0]:+.1f} / {a[1] - c[1]:+.1f} / {a[2] - c[2]:+.1f} / {a[3] - c[3]:+.1f}"
                             for a, c in zip(f, g))]
