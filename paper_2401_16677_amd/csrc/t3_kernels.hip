@@ -16,6 +16,9 @@
 // and from the accumulator layout through LDS.  A persistent workgroup requests the next
 // tile's incoming partial right behind the current tile's stores.
 //
+// A persistent launch whose last round of tiles would fill at most half the chip computes each
+// of those tiles as two halves of K on two workgroups (balanced tail, see work_item).
+//
 // Included by t3_api.hip only.
 #pragma once
 
