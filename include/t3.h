@@ -18,8 +18,11 @@
  *
  * Conventions for every entry point
  *  - Pointers named A, B, C, R, fwd, track are DEVICE pointers owned by the caller.
- *    The library allocates and frees nothing.  The only state it keeps is read-only after first
- *    use: the compute-unit and XCD counts of each device it has launched on, and T3_STAGGER.
+ *    The library allocates and frees no device memory.  What it keeps: the compute-unit and XCD
+ *    counts of each device it has launched on and T3_STAGGER (read-only after first use); two
+ *    small arrays inside its own code object per device (the tracker state of
+ *    t3_gemm_rs_fused_static; flag words for t3_gemm's balanced tail, with one HIP event per
+ *    set of flags, created at first use); and the pointer given to t3_timeline.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *    asynchronous on that stream and never synchronise it.
  *  - Arguments are validated on the host before anything is enqueued; on any status
