@@ -422,3 +422,21 @@ def test_balanced_tail_in_a_captured_graph(gpu, oracle, unfused):
         restore()
         step()
         check(f"eager after replay {rep}")
+
+
+@pytest.mark.parametrize("direct", [False, True])
+def test_balanced_tail_single_rank_in_place(gpu, oracle, direct):
+    """tp = 1: one chunk, the rank's own, reduced in place in R (no release work in either mode,
+    so the launch is persistent and balances its tail); the partial sums of the split tiles pass
+    through the very place the incoming partial was read from."""
+    tile, (M, N, K, tp, rank) = (256, 256), (4090, 10240, 520, 1, 0)
+    assert _workgroup_tiles(M, N, tp, tile) == 2 * CUS + 128
+    print(f"tile={tile} shape={(M, N, K, tp, rank)} direct={direct}", flush=True)
+    a, b, inc = wl.make_integer_inputs(M, N, K, seed=1800)
+    want = oracle.fused_path(a, b, inc, tp, rank, *tile, fwd_direct=direct,
+                             fwd_init=np.full((0, M, N), gpu.SENTINEL, np.float32))
+    got = gpu.run_gpu(a, b, inc, tp, rank, tile, flags=t3.T3_FLAG_FWD_DIRECT if direct else 0,
+                      ldr_pad=4, launches_before=1)
+    assert np.array_equal(got["R"], want["R"]), _first_mismatch(got["R"], want["R"])
+    assert np.all(got["R_pad"] == 123.0)
+    _check_ints(got, want, want["own"])
